@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the blocked SpMM path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--no-cpu-baseline]
+
+Prints ONE JSON line.  The metric is VBR-SpMM throughput in TFLOP/s on stored-block flops
+(2 * stored elements * N per multiply); a step is one ``vbr_spmm`` launch on the resident VBR
+matrix with A (packed), B and C already in HBM.  The one-off host work of the path (1-SA
+reordering, VBR build, upload), which the method discounts over many multiplications (section 6
+of the paper), is timed once and reported under ``setup``.  The CPU oracle is timed beside it on
+a bounded sample of the same workload (``cpu_baseline``); it is a checker, not a target.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16 / bf16 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+WORKLOAD_TEXT = {
+    "c1": "configs[0]: A 1024x1024 fp16, 32x32 planted blocks at 10%, +0.5% noise, N=256, tau=0.7",
+    "c2": "configs[1]: A 8192x8192 fp16, 64x64 planted blocks at 5%, +1% off-block noise, N=1024, tau=0.6",
+    "c3": "configs[2]: A 16384x16384 bf16, heights {16,32,64,128} x 32 blocks at 2%, fill 0.7, N=512, tau=0.6",
+    "c4": "configs[3]: pruned-weight-like A 4096x16384 fp16, 16x16 blocks kept at 10%, N=4096, tau=0.5",
+    "c5": "configs[4]: Erdos-Renyi A 32768x32768 fp16 density 0.05%, column block 32, N=256, tau=0.3",
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--clean", action="store_true", help="noise-free variant of c1/c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (row groups shard "
+              "without any exchange step, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2202_05868_amd import binding, synth, torch_io
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = synth.workload(args.workload, noise=not args.clean)
+    a, cb, n = w["A"], w["col_block"], w["N"]
+    tau = w["taus"][len(w["taus"]) // 2]
+
+    # ---- one-off host work of the path
+    t0 = time.perf_counter()
+    perm, rg = binding.sa1_reorder(a, cb, tau)
+    t1 = time.perf_counter()
+    v = binding.vbr_build(a, perm, rg, cb)
+    t2 = time.perf_counter()
+    v.upload(dev)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    ix = v.index()
+    stored = int(ix["stored_elems"])
+    h = np.diff(rg)
+
+    b = torch_io.bits_to_device(w["B"], w["dtype"], dev)
+    c = torch.empty((a["n_rows"], n), dtype=torch.float32, device=dev)
+
+    # ---- timed region: K launches between HIP events on the launch stream
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        v.spmm(b, c)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        v.spmm(b, c)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall1 = time.perf_counter()
+    ms = ev0.elapsed_time(ev1) / args.steps
+    wall_ms = (wall1 - wall0) * 1e3 / args.steps
+
+    flops_stored = 2.0 * stored * n
+    flops_nnz = 2.0 * a["nnz"] * n
+    tflops = flops_stored / (ms * 1e-3) * 1e-12
+    tflops_nnz = flops_nnz / (ms * 1e-3) * 1e-12
+    # compulsory HBM bytes of one multiply: packed A once, B once, C once
+    hbm_min = v.schedule()["packed_elems"] * 2 + a["n_cols"] * n * 2 + a["n_rows"] * n * 4
+    # the bound: the MFMA time of the stored flops against the compulsory HBM time
+    t_mfma = flops_stored / (PEAK_MFMA_F16_TFLOPS * 1e12)
+    t_hbm = hbm_min / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        roofline = dict(bound="mfma", achieved=tflops, peak=PEAK_MFMA_F16_TFLOPS, unit="TFLOP/s",
+                        frac=tflops / PEAK_MFMA_F16_TFLOPS, traffic=None)
+    else:
+        gbs = hbm_min / (ms * 1e-3) * 1e-9
+        roofline = dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
+                        traffic=None)
+    roofline["kernel"] = "vbr_spmm_kernel"
+    roofline["ms_per_launch"] = ms
+    roofline["algorithmic_flops"] = flops_stored
+    roofline["algorithmic_hbm_bytes"] = hbm_min
+    tr = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % args.workload)
+    if os.path.exists(tr):       # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/)
+        try:
+            roofline["traffic"] = json.load(open(tr)).get("hbm_bytes_per_launch")
+        except Exception:
+            pass
+
+    out = {
+        "metric": "VBR-SpMM TFLOP/s (stored-block flops 2*stored_elems*N)",
+        "value": tflops,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w["dtype"] + " x " + w["dtype"] + " -> f32 (MFMA)",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + ("" if not args.clean else " (noise-free)"),
+                   "N": n, "col_block": cb, "tau": tau, "parallelism": "1 GPU"},
+        "nnz_effective_tflops": tflops_nnz,
+        "pct_mfma_fp16_peak": 100.0 * tflops / PEAK_MFMA_F16_TFLOPS,
+        "pct_hbm_peak_compulsory": 100.0 * (hbm_min / (ms * 1e-3) * 1e-9) / PEAK_HBM_GBS,
+        "wall_ms_per_step": wall_ms,
+        "blocking": {"groups": int(len(h)), "mean_height": float(h.mean()) if len(h) else 0.0,
+                     "max_height": int(h.max()) if len(h) else 0, "blocks": int(ix["n_blocks"]),
+                     "stored_elems": stored, "nnz": int(a["nnz"]),
+                     "fill_overhead": stored / max(1, a["nnz"]), **v.schedule()},
+        "setup": {"sa1_reorder_s": t1 - t0, "vbr_build_s": t2 - t1, "upload_s": t3 - t2},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: as many whole rows of the same workload as take roughly 10-20 s
+        rows_all = np.arange(a["n_rows"])
+        probe = rows_all[:: max(1, a["n_rows"] // 64)][:64]
+        t = time.perf_counter()
+        oracle.spmm(a, w["B"], rows=probe)
+        dt = max(time.perf_counter() - t, 1e-4)   # includes the 16-bit -> binary64 conversion of B
+        nnz_probe = int(np.diff(a["row_ptr"])[probe].sum())
+        t = time.perf_counter()
+        oracle.spmm(a, w["B"], rows=probe)
+        dt = max(time.perf_counter() - t, 1e-4)
+        per_nnz = dt / max(1, nnz_probe)
+        target_nnz = 12.0 / per_nnz
+        lens = np.diff(a["row_ptr"])
+        k = int(np.searchsorted(np.cumsum(lens), target_nnz)) + 1
+        sample = rows_all[: min(k, a["n_rows"])]
+        t = time.perf_counter()
+        oracle.spmm(a, w["B"], rows=sample)
+        dt = time.perf_counter() - t
+        nnz_s = int(lens[sample].sum())
+        out["cpu_baseline"] = {
+            "value": 2.0 * nnz_s * n / dt * 1e-12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "first %d of %d rows (%d nonzeros), fp64 C = A.B and bound |A|.|B| from CSR, OpenMP over rows, "
+                      "%.1f s incl. 16-bit->fp64 conversion of B; flops counted as 2*nnz*N" % (
+                          sample.size, a["n_rows"], nnz_s, dt),
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,136 @@
+/*
+ * vbr_spmm.h -- C ABI of the blocked sparse-times-dense path for one MI355X (gfx950).
+ *
+ * The path, after "Blocking Techniques for Sparse Matrix Multiplication on Tensor
+ * Accelerators" (arXiv 2202.05868):
+ *
+ *   sa1_reorder   1-SA row reordering: quotient rows over a regular column partition (section
+ *                 3.1, Eq. 4), grouping of identical quotient rows (Algorithm 1 applied to
+ *                 quotient rows, hash of Eq. 5), greedy merge with pattern update (Algorithm 2)
+ *                 under the two-step merge condition (section 3.2: Jaccard similarity, Eq. 3,
+ *                 and the limit lambda <= lambda0 / (1 - tau/2) that gives Theorem 1).
+ *   vbr_build     row partition + column partition -> variable-block-row matrix that keeps
+ *                 only the nonzero blocks, zero-filled (section 2, section 3.1 last paragraph).
+ *   vbr_spmm      C = A.B, every stored block multiplied as a small dense product on the
+ *                 matrix units (section 4.4.1), in one kernel launch.
+ *
+ * sa1_reorder and vbr_build are deterministic integer host code.  vbr_spmm runs on the GPU.
+ * All pointers are HOST pointers unless the name ends in _dev.  Nothing is retained from the
+ * caller's arrays after a call returns, except the device buffer handed to vbr_upload.
+ * No call throws or aborts; every call returns 0 (VBR_OK) or a negative error code.
+ * Calls on distinct handles may run concurrently; a handle is not internally locked.
+ */
+#ifndef VBR_SPMM_H
+#define VBR_SPMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    VBR_OK = 0,
+    VBR_EINVAL = -1,       /* bad argument, non-canonical CSR, perm not a bijection, ... */
+    VBR_ENOMEM = -2,       /* host allocation failed */
+    VBR_EHIP = -3,         /* a HIP runtime call failed (vbr_last_hip_error has its code) */
+    VBR_ESTATE = -4,       /* call out of order (e.g. vbr_spmm before vbr_upload) */
+    VBR_EUNSUPPORTED = -5  /* valid input the GPU path does not take (see vbr_upload) */
+};
+
+enum { VBR_F16 = 0, VBR_BF16 = 1 };
+
+/*
+ * Sparse matrix in CSR (section 2), borrowed from the caller, host memory.
+ * Canonical form is required: row_ptr[0] == 0, row_ptr non-decreasing, row_ptr[n_rows] == nnz,
+ * column indices strictly increasing inside a row and in [0, n_cols).  Every stored entry is a
+ * structural nonzero, whatever its value.
+ */
+typedef struct vbr_csr {
+    int64_t n_rows, n_cols, nnz;
+    const int64_t *row_ptr;   /* [n_rows + 1] */
+    const int32_t *col_idx;   /* [nnz] */
+    const void *vals;         /* [nnz] 16-bit patterns of type dtype; may be NULL for sa1_reorder */
+    int32_t dtype;            /* VBR_F16 or VBR_BF16 */
+} vbr_csr_t;
+
+typedef struct vbr vbr_t;     /* host handle of a built VBR matrix, owned by the library */
+
+/*
+ * 1-SA (Algorithm 2 with the merge condition of section 3.2) on the quotient rows of `csr`
+ * over column blocks of width col_block (n_cols % col_block must be 0).
+ *
+ *   tau         Jaccard threshold in [0, 1].  A row joins a group when
+ *               |P & v| / |P | v| >= tau (one binary64 division; two empty patterns are similar)
+ *               and |P | v| <= floor(lambda0 / (1 - tau/2)), lambda0 = blocks of the group's seed.
+ *   perm        out [n_rows]: perm[new position] = original row.  Groups are numbered in seed
+ *               order (by smallest original row), rows ascend inside a group.
+ *   row_groups  out, room for n_rows + 1 entries: row_groups[g] = first position of group g,
+ *               row_groups[*n_groups] = n_rows.
+ * Identical quotient rows are grouped first and visited as one row, in order of their
+ * smallest member (section 3.1).  csr->vals is not read.
+ */
+int sa1_reorder(const vbr_csr_t *csr, int32_t col_block, double tau,
+                int32_t *perm, int32_t *row_groups, int32_t *n_groups);
+
+/*
+ * Build the VBR matrix of `csr` for ANY valid row partition (perm a bijection of the rows,
+ * row_groups strictly increasing from 0 to n_rows) and the regular column partition of width
+ * col_block.  Per group the stored blocks are the column blocks that hold at least one entry of
+ * the group's rows, ascending; a block of group g is the h_g x col_block window of the permuted
+ * matrix, zero-filled (section 2: fill-in).  Values are packed in the layout the kernel reads.
+ * On success *out is a new handle; free it with vbr_free.
+ */
+int vbr_build(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups,
+              int32_t n_groups, int32_t col_block, vbr_t **out);
+
+/*
+ * Views of the index arrays, valid until vbr_free.  Any out pointer may be NULL.
+ *   row_groups [n_groups + 1], perm [n_rows]          as given to vbr_build
+ *   blk_ptr    [n_groups + 1]   blocks of group g are blk_ptr[g] .. blk_ptr[g+1]-1
+ *   blk_col    [n_blocks]       column block of each stored block, ascending inside a group
+ *   blk_off    [n_blocks + 1]   running element offset; block b holds h_g * col_block elements
+ */
+int vbr_get_index(const vbr_t *v, const int32_t **row_groups, const int32_t **perm,
+                  const int64_t **blk_ptr, const int32_t **blk_col, const int64_t **blk_off,
+                  int64_t *n_groups, int64_t *n_blocks, int64_t *stored_elems);
+
+/* Copy stored block `blk` out of the packed kernel layout: dst[h_g * col_block] 16-bit, row-major. */
+int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst);
+
+/* Bytes of device memory vbr_upload needs (a multiple of 256, never 0). */
+int64_t vbr_device_bytes(const vbr_t *v);
+
+/*
+ * Copy the packed matrix and its schedule into buf_dev (device memory of the current device,
+ * allocated by the caller, at least vbr_device_bytes(v) bytes, 256-byte aligned) on hip_stream
+ * (a hipStream_t, NULL = default stream) and wait for the copy.  The handle keeps the pointer;
+ * the buffer must outlive every vbr_spmm on this handle.  The library allocates no device memory.
+ * Any col_block >= 1 is taken (widths that are multiples of 32 gather B rows most cheaply).
+ */
+int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
+
+/*
+ * C = A.B on the GPU (section 4.4.1), asynchronous on hip_stream, no synchronisation.
+ *   B_dev  K x N row-major, 16-bit type of the matrix, leading dimension ldb (elements)
+ *   C_dev  n_rows x N row-major fp32, leading dimension ldc (elements); OVERWRITTEN (beta = 0),
+ *          rows in ORIGINAL row order (the reordering is internal); rows without entries get 0
+ * Requires N >= 0, N % 8 == 0, ldb >= N, ldb % 8 == 0, ldc >= N, ldc % 4 == 0, B_dev and C_dev
+ * 16-byte aligned (else VBR_EINVAL).  Products are exact, sums are fp32 on the matrix units.
+ * B and C must not overlap each other or the uploaded buffer.
+ */
+int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,
+             int64_t N, void *hip_stream);
+
+/* Number of workgroup tiles and K-steps of the schedule (for reporting). */
+int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems);
+
+void vbr_free(vbr_t *v);
+
+const char *vbr_strerror(int code);
+int vbr_last_hip_error(void);   /* hipError_t of the last failing HIP call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VBR_SPMM_H */

@@ -1,0 +1,261 @@
+// VBR construction on the host: index arrays of the format (section 2 and the last paragraph of
+// section 3.1 of the paper), values packed as MFMA fragments, and the workgroup schedule.
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "vbr_host.h"
+
+namespace vbrk {
+namespace {
+
+inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+inline int slab_class(int n_slabs)   // kernels exist for 1, 2, 4 and 8 slabs
+{
+    return n_slabs <= 1 ? 0 : n_slabs <= 2 ? 1 : n_slabs <= 4 ? 2 : 3;
+}
+
+int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups, int32_t G,
+               int32_t col_block, vbr *v)
+{
+    const int64_t M = csr->n_rows;
+    const int64_t KB = csr->n_cols / col_block;
+    v->n_rows = M;
+    v->n_cols = csr->n_cols;
+    v->nnz = csr->nnz;
+    v->col_block = col_block;
+    v->dtype = csr->dtype;
+    v->n_groups = G;
+    v->perm.assign(perm, perm + M);
+    v->row_groups.assign(row_groups, row_groups + G + 1);
+
+    // B rows are gathered in granules of 2^lg_gran consecutive rows: the largest power of two
+    // that divides the block width, at most one K-step.
+    int lg = 0;
+    while (lg < 5 && col_block % (2 << lg) == 0) ++lg;
+    v->lg_gran = lg;
+    const int gran = 1 << lg;
+    const int per_step = kStepK >> lg;   // krow entries per K-step
+
+    v->blk_ptr.assign((size_t)G + 1, 0);
+    v->blk_off.assign(1, 0);
+    v->ks_ptr.assign((size_t)G + 1, 0);
+    v->group_first_tile.assign((size_t)G + 1, 0);
+    std::vector<int32_t> pos_of_block((size_t)std::max<int64_t>(KB, 1), -1);
+    std::vector<int32_t> blocks;
+    std::vector<TileDesc> tiles;
+    int64_t a_units = 0;   // running size of the packed values, in units of 8 values
+
+    // pass 1: index arrays, K-step gather lists, tiles
+    for (int32_t g = 0; g < G; ++g) {
+        const int64_t r0 = row_groups[g], r1 = row_groups[g + 1];
+        const int64_t h = r1 - r0;
+        blocks.clear();
+        for (int64_t q = r0; q < r1; ++q) {
+            const int64_t r = perm[q];
+            int64_t last = -1;
+            for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                const int64_t j = csr->col_idx[p] / col_block;
+                if (j != last) {
+                    if (pos_of_block[j] < 0) { pos_of_block[j] = 0; blocks.push_back((int32_t)j); }
+                    last = j;
+                }
+            }
+        }
+        std::sort(blocks.begin(), blocks.end());
+        for (int32_t j : blocks) pos_of_block[j] = -1;
+        const int64_t nb = (int64_t)blocks.size();
+        for (int64_t t = 0; t < nb; ++t) {
+            v->blk_col.push_back(blocks[t]);
+            v->blk_off.push_back(v->blk_off.back() + h * col_block);
+        }
+        v->blk_ptr[g + 1] = v->blk_ptr[g] + nb;
+
+        const int64_t Kg = nb * col_block;
+        const int64_t n_ks = (Kg + kStepK - 1) / kStepK;
+        if (v->ks_ptr[g] + n_ks > INT32_MAX / 64) return VBR_EINVAL;
+        v->ks_ptr[g + 1] = v->ks_ptr[g] + n_ks;
+        for (int64_t e = 0; e < n_ks * per_step; ++e) {
+            const int64_t k = e * gran;
+            if (k < Kg) v->krow.push_back((int32_t)((int64_t)blocks[k / col_block] * col_block + k % col_block));
+            else v->krow.push_back(-1);
+        }
+
+        const int64_t slabs = (h + kSlabRows - 1) / kSlabRows;
+        const int64_t nt = (slabs + kMaxSlabs - 1) / kMaxSlabs;
+        v->group_first_tile[g + 1] = v->group_first_tile[g] + nt;
+        int64_t row = 0;
+        for (int64_t t = 0; t < nt; ++t) {
+            const int64_t s = slabs / nt + (t < slabs % nt ? 1 : 0);
+            TileDesc td;
+            td.ks_begin = (int32_t)v->ks_ptr[g];
+            td.n_ks = (int32_t)n_ks;
+            td.a_off = a_units;
+            td.row_begin = (int32_t)(r0 + row);
+            td.n_rows = (int32_t)std::min<int64_t>(s * kSlabRows, h - row);
+            td.n_slabs = (int32_t)s;
+            td.group = g;
+            a_units += n_ks * tile_kstep_stride(td.n_rows, td.n_slabs) / 8;
+            row += td.n_rows;
+            tiles.push_back(td);
+        }
+    }
+
+    // pass 2: values into fragments
+    v->vals.assign((size_t)a_units * 8, 0);
+    const uint16_t *src = static_cast<const uint16_t *>(csr->vals);
+    for (int32_t g = 0; g < G; ++g) {
+        for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) pos_of_block[v->blk_col[b]] = (int32_t)(b - v->blk_ptr[g]);
+        for (int64_t t = v->group_first_tile[g]; t < v->group_first_tile[g + 1]; ++t) {
+            const TileDesc &td = tiles[t];
+            const int64_t stride = tile_kstep_stride(td.n_rows, td.n_slabs);
+            const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
+            uint16_t *dst = &v->vals[(size_t)td.a_off * 8];
+            for (int32_t rr = 0; rr < td.n_rows; ++rr) {
+                const int64_t r = perm[td.row_begin + rr];
+                const int slab = rr / kSlabRows, m = rr % kSlabRows;
+                const int rows = slab == td.n_slabs - 1 ? rows_last : kSlabRows;
+                for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                    const int64_t c = csr->col_idx[p];
+                    const int64_t k = (int64_t)pos_of_block[c / col_block] * col_block + c % col_block;
+                    dst[(k / kStepK) * stride + (int64_t)slab * kFragElems + frag_index(m, (int)(k % kStepK), rows)] = src[p];
+                }
+            }
+        }
+        for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) pos_of_block[v->blk_col[b]] = -1;
+    }
+
+    // schedule: tiles grouped by slab class (one kernel instantiation each), heaviest first
+    const int64_t NT = (int64_t)tiles.size();
+    std::vector<int32_t> order(NT);
+    for (int64_t i = 0; i < NT; ++i) order[i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        const int ca = slab_class(tiles[a].n_slabs), cb = slab_class(tiles[b].n_slabs);
+        if (ca != cb) return ca < cb;
+        const int64_t wa = (int64_t)tiles[a].n_ks * tiles[a].n_slabs, wb = (int64_t)tiles[b].n_ks * tiles[b].n_slabs;
+        return wa > wb;
+    });
+    v->tiles.resize(NT);
+    v->tile_of_group_order.resize(NT);
+    for (int c = 0; c < 5; ++c) v->class_begin[c] = 0;
+    for (int64_t i = 0; i < NT; ++i) {
+        v->tiles[i] = tiles[order[i]];
+        v->tile_of_group_order[order[i]] = (int32_t)i;
+        v->class_begin[slab_class(tiles[order[i]].n_slabs) + 1]++;
+    }
+    for (int c = 0; c < 4; ++c) v->class_begin[c + 1] += v->class_begin[c];
+
+    DeviceLayout &L = v->lay;
+    L.tiles_off = 0;
+    L.krow_off = align_up(L.tiles_off + NT * (int64_t)sizeof(TileDesc), 256);
+    L.perm_off = align_up(L.krow_off + (int64_t)v->krow.size() * 4, 256);
+    L.vals_off = align_up(L.perm_off + M * 4, 256);
+    L.total = std::max<int64_t>(256, align_up(L.vals_off + (int64_t)v->vals.size() * 2, 256));
+    return VBR_OK;
+}
+
+}  // namespace
+}  // namespace vbrk
+
+extern "C" int vbr_build(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups,
+                         int32_t n_groups, int32_t col_block, vbr_t **out)
+{
+    if (!csr || !out || n_groups < 0 || col_block <= 0) return VBR_EINVAL;
+    *out = nullptr;
+    int rc = vbrk::validate_csr(csr, true);
+    if (rc != VBR_OK) return rc;
+    if (csr->n_cols % col_block != 0) return VBR_EINVAL;
+    const int64_t M = csr->n_rows;
+    if ((M > 0 && (!perm || !row_groups)) || !row_groups) return VBR_EINVAL;
+    if (n_groups > M || (M > 0 && n_groups == 0)) return VBR_EINVAL;
+    if (row_groups[0] != 0 || row_groups[n_groups] != M) return VBR_EINVAL;
+    for (int32_t g = 0; g < n_groups; ++g)
+        if (row_groups[g + 1] <= row_groups[g]) return VBR_EINVAL;
+    try {
+        std::vector<uint8_t> seen((size_t)M, 0);
+        for (int64_t i = 0; i < M; ++i) {
+            if (perm[i] < 0 || perm[i] >= M || seen[perm[i]]) return VBR_EINVAL;   // not a bijection
+            seen[perm[i]] = 1;
+        }
+        vbr *v = new vbr();
+        rc = vbrk::build_impl(csr, perm, row_groups, n_groups, col_block, v);
+        if (rc != VBR_OK) { delete v; return rc; }
+        *out = v;
+        return VBR_OK;
+    } catch (const std::bad_alloc &) {
+        return VBR_ENOMEM;
+    } catch (...) {
+        return VBR_EINVAL;
+    }
+}
+
+extern "C" int vbr_get_index(const vbr_t *v, const int32_t **row_groups, const int32_t **perm,
+                             const int64_t **blk_ptr, const int32_t **blk_col, const int64_t **blk_off,
+                             int64_t *n_groups, int64_t *n_blocks, int64_t *stored_elems)
+{
+    if (!v) return VBR_EINVAL;
+    if (row_groups) *row_groups = v->row_groups.data();
+    if (perm) *perm = v->perm.data();
+    if (blk_ptr) *blk_ptr = v->blk_ptr.data();
+    if (blk_col) *blk_col = v->blk_col.data();
+    if (blk_off) *blk_off = v->blk_off.data();
+    if (n_groups) *n_groups = v->n_groups;
+    if (n_blocks) *n_blocks = (int64_t)v->blk_col.size();
+    if (stored_elems) *stored_elems = v->blk_off.back();
+    return VBR_OK;
+}
+
+extern "C" int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst_)
+{
+    using namespace vbrk;
+    if (!v || !dst_ || blk < 0 || blk >= (int64_t)v->blk_col.size()) return VBR_EINVAL;
+    const int32_t g = (int32_t)(std::upper_bound(v->blk_ptr.begin(), v->blk_ptr.end(), blk) - v->blk_ptr.begin() - 1);
+    const int64_t pos = blk - v->blk_ptr[g];
+    const int64_t cb = v->col_block;
+    uint16_t *dst = static_cast<uint16_t *>(dst_);
+    int64_t row = 0;
+    for (int64_t t = v->group_first_tile[g]; t < v->group_first_tile[g + 1]; ++t) {
+        const TileDesc &td = v->tiles[v->tile_of_group_order[t]];
+        const int64_t stride = tile_kstep_stride(td.n_rows, td.n_slabs);
+        const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
+        const uint16_t *src = &v->vals[(size_t)td.a_off * 8];
+        for (int32_t rr = 0; rr < td.n_rows; ++rr, ++row) {
+            const int slab = rr / kSlabRows, m = rr % kSlabRows;
+            const int rows = slab == td.n_slabs - 1 ? rows_last : kSlabRows;
+            for (int64_t c = 0; c < cb; ++c) {
+                const int64_t k = pos * cb + c;
+                dst[row * cb + c] = src[(k / kStepK) * stride + (int64_t)slab * kFragElems + frag_index(m, (int)(k % kStepK), rows)];
+            }
+        }
+    }
+    return VBR_OK;
+}
+
+extern "C" int64_t vbr_device_bytes(const vbr_t *v) { return v ? v->lay.total : 0; }
+
+extern "C" int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems)
+{
+    if (!v) return VBR_EINVAL;
+    if (n_tiles) *n_tiles = (int64_t)v->tiles.size();
+    if (n_ksteps) *n_ksteps = v->ks_ptr.back();
+    if (packed_elems) *packed_elems = (int64_t)v->vals.size();
+    return VBR_OK;
+}
+
+extern "C" void vbr_free(vbr_t *v) { delete v; }
+
+extern "C" const char *vbr_strerror(int code)
+{
+    switch (code) {
+    case VBR_OK: return "ok";
+    case VBR_EINVAL: return "invalid argument";
+    case VBR_ENOMEM: return "out of host memory";
+    case VBR_EHIP: return "HIP runtime error";
+    case VBR_ESTATE: return "call out of order";
+    case VBR_EUNSUPPORTED: return "unsupported input";
+    default: return "unknown error";
+    }
+}

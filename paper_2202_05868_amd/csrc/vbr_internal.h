@@ -1,0 +1,78 @@
+// Internal layout of a built VBR matrix: the index arrays of the format, the packed values in
+// the order the MFMA kernel reads them, and the workgroup schedule.  Host and device code of the
+// library share this header; nothing outside the library includes it.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "vbr_spmm.h"
+
+namespace vbrk {
+
+constexpr int kSlabRows = 16;       // rows of one MFMA slab
+constexpr int kStepK = 32;          // B rows consumed per K-step (one 16x16x32 MFMA deep)
+constexpr int kMaxSlabs = 8;        // slabs per workgroup tile (128 rows)
+constexpr int kFragElems = kSlabRows * kStepK;   // 512 16-bit values = 1 KiB per (slab, K-step)
+
+// One workgroup tile: up to kMaxSlabs slabs of ONE row group, walked over the group's K-steps.
+struct TileDesc {
+    int32_t ks_begin;    // first K-step of the tile's group (global K-step number)
+    int32_t n_ks;        // K-steps of the group
+    int64_t a_off;       // first value of the tile, in units of 8 values (16 bytes)
+    int32_t row_begin;   // position in perm of the tile's first row
+    int32_t n_rows;      // rows of the tile, 1 .. 16 * n_slabs
+    int32_t n_slabs;     // ceil(n_rows / 16)
+    int32_t group;       // row group the tile belongs to
+};
+static_assert(sizeof(TileDesc) == 32, "TileDesc is read by the kernel as 2 x 16 bytes");
+
+// Position inside a (slab, K-step) fragment of the value at slab row m and K-step-local column
+// kk (0..31 = row of the staged B panel), for a slab that stores `rows` rows (16, or fewer for the
+// last slab of a tile: padding rows are not stored).  Lane l = m + 16 q of the wave holds 8 values
+// (slots 0..7) of slab row m; a fragment is laid out [q][m][slot], so it takes rows * 32 values.
+// The K order inside the step is permuted so that the four B rows a 16-lane group reads with one
+// transposed LDS read, together with those of its neighbour group, fall into distinct LDS banks:
+//   kk = 8 u + 4 v + e  ->  q = 2 (u / 2) + v,  slot = 4 (u % 2) + e.
+inline int frag_index(int m, int kk, int rows)
+{
+    int u = kk >> 3, v = (kk >> 2) & 1, e = kk & 3;
+    int q = 2 * (u >> 1) + v;
+    int slot = 4 * (u & 1) + e;
+    return ((q * rows + m) << 3) + slot;
+}
+
+// Values per K-step of a tile: full slabs take 512, the last slab rows_last * 32.
+inline int64_t tile_kstep_stride(int32_t n_rows, int32_t n_slabs)
+{
+    int rows_last = n_rows - (n_slabs - 1) * kSlabRows;
+    return (int64_t)(n_slabs - 1) * kFragElems + (int64_t)rows_last * kStepK;
+}
+
+// Byte offsets of the sections inside the device buffer (each 256-byte aligned).
+struct DeviceLayout {
+    int64_t tiles_off = 0, krow_off = 0, perm_off = 0, vals_off = 0, total = 0;
+};
+
+}  // namespace vbrk
+
+struct vbr {
+    int64_t n_rows = 0, n_cols = 0, nnz = 0;
+    int32_t col_block = 0, dtype = 0;
+    int32_t n_groups = 0;
+    // the VBR index (bit-exact part of the format)
+    std::vector<int32_t> perm, row_groups;
+    std::vector<int64_t> blk_ptr, blk_off;
+    std::vector<int32_t> blk_col;
+    // kernel-side data
+    int32_t lg_gran = 0;                 // log2 of the B-row gather granularity (rows per krow entry)
+    std::vector<int64_t> ks_ptr;         // [n_groups+1] first global K-step of each group
+    std::vector<int32_t> krow;           // first B row of each granule of each K-step, -1 = padding
+    std::vector<vbrk::TileDesc> tiles;    // sorted by slab class, then by falling work
+    int32_t class_begin[5] = {0, 0, 0, 0, 0};  // tiles of slab class c (1,2,4,8 slabs) are [class_begin[c], class_begin[c+1])
+    std::vector<int64_t> group_first_tile;      // [n_groups+1] tiles of a group in creation order (for unpack)
+    std::vector<int32_t> tile_of_group_order;   // creation order -> index in `tiles`
+    std::vector<uint16_t> vals;          // packed fragments
+    vbrk::DeviceLayout lay;
+    void *dev = nullptr;                 // uploaded buffer (caller-owned)
+};

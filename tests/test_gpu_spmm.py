@@ -1,0 +1,174 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the same seeded inputs.
+
+Bar: perm, row_groups and the VBR index arrays bit-exact; |C - C_ref| <= 1e-4 * sum_k |a_ik||b_kj|
+elementwise (C_ref and the bound in binary64 from the original CSR).  Small cases are compared
+element by element; the full-size workloads on sampled rows the oracle computes one by one.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2202_05868_amd import binding, synth, torch_io
+from helpers import csr_from_rows, random_csr
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def gpu_spmm(csr, perm, rg, col_block, b_bits, ldb_pad=0, ldc_pad=0):
+    import torch
+    v = binding.vbr_build(csr, perm, rg, col_block).upload("cuda:0")
+    k, n = b_bits.shape
+    if ldb_pad:
+        full = np.zeros((k, n + ldb_pad), dtype=np.uint16)
+        full[:, :n] = b_bits
+        b = torch_io.bits_to_device(full, csr["dtype"])[:, :n]
+    else:
+        b = torch_io.bits_to_device(b_bits, csr["dtype"])
+    c_full = torch.full((csr["n_rows"], n + ldc_pad), float("nan"), dtype=torch.float32, device="cuda:0")
+    c = c_full[:, :n]
+    v.spmm(b, c)
+    torch.cuda.synchronize()
+    out = c_full.cpu().numpy()
+    if ldc_pad:
+        assert np.isnan(out[:, n:]).all(), "wrote outside the N columns"
+    return out[:, :n].astype(np.float64), v
+
+
+def check_c(c, c_ref, s, what=""):
+    assert not np.isnan(c).any(), what + ": NaN left in C (rows not written)"
+    err = np.abs(c - c_ref)
+    bad = err > TOL * s
+    assert not bad.any(), "%s: %d elements outside the bound, worst err/bound %.3g" % (
+        what, int(bad.sum()), float(np.max(err / np.maximum(s, 1e-300))))
+
+
+def blocking_bit_exact(csr, col_block, tau):
+    p0, g0 = oracle.sa1(csr, col_block, tau)
+    perm, rg = binding.sa1_reorder(csr, col_block, tau)
+    assert np.array_equal(perm, p0) and np.array_equal(rg, g0)
+    return perm, rg
+
+
+def index_bit_exact(v, csr, perm, rg, col_block):
+    bp, bc, bo = oracle.vbr_index(csr, perm, rg, col_block)
+    ix = v.index()
+    assert np.array_equal(ix["blk_ptr"], bp) and np.array_equal(ix["blk_col"], bc) and np.array_equal(ix["blk_off"], bo)
+
+
+# --------------------------------------------------------------------------- small, element by element
+@pytest.mark.parametrize("col_block", [1, 3, 8, 16, 32, 64])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_random_matrices_all_column_block_widths(col_block, dtype):
+    rng = np.random.default_rng(col_block * 7 + (dtype == "bf16"))
+    for m, kb, n, dens, tau in [(70, 9, 64, 0.2, 0.4), (300, 5, 264, 0.05, 0.2), (33, 12, 8, 0.6, 0.7)]:
+        csr = random_csr(rng, m, kb * col_block, dens, dtype=dtype)
+        b = synth.dense_rhs(rng, kb * col_block, n, dtype)
+        perm, rg = blocking_bit_exact(csr, col_block, tau)
+        c, v = gpu_spmm(csr, perm, rg, col_block, b)
+        index_bit_exact(v, csr, perm, rg, col_block)
+        c_ref, s = oracle.spmm(csr, b)
+        check_c(c, c_ref, s, "cb=%d %s m=%d n=%d" % (col_block, dtype, m, n))
+
+
+def test_result_does_not_depend_on_the_row_partition_used():
+    rng = np.random.default_rng(5)
+    csr = random_csr(rng, 500, 256, 0.04)
+    b = synth.dense_rhs(rng, 256, 520, "f16")           # 520: two full column tiles + ragged tail
+    c_ref, s = oracle.spmm(csr, b)
+    ident = (np.arange(500, dtype=np.int32), np.arange(501, dtype=np.int32))          # every row its own group
+    one = (np.arange(500, dtype=np.int32), np.array([0, 500], dtype=np.int32))        # one group of 500 rows
+    rnd = (rng.permutation(500).astype(np.int32), np.array([0, 1, 18, 150, 151, 300, 500], dtype=np.int32))
+    sa = blocking_bit_exact(csr, 16, 0.3)
+    for name, (perm, rg) in [("identity", ident), ("one group", one), ("random", rnd), ("1-SA", sa)]:
+        c, v = gpu_spmm(csr, perm, rg, 16, b)
+        index_bit_exact(v, csr, perm, rg, 16)
+        check_c(c, c_ref, s, name)
+
+
+def test_leading_dimensions_and_overwrite():
+    rng = np.random.default_rng(6)
+    csr = random_csr(rng, 90, 128, 0.1, dtype="bf16")
+    b = synth.dense_rhs(rng, 128, 72, "bf16", dist="normal")
+    perm, rg = blocking_bit_exact(csr, 32, 0.5)
+    c, _ = gpu_spmm(csr, perm, rg, 32, b, ldb_pad=24, ldc_pad=12)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "padded leading dimensions")
+
+
+def test_empty_rows_get_zeros_and_single_dense_block_is_a_gemm():
+    rng = np.random.default_rng(7)
+    csr = csr_from_rows([[], [1, 40], [], [2], []], n_cols=64, rng=rng)
+    b = synth.dense_rhs(rng, 64, 16, "f16")
+    perm, rg = blocking_bit_exact(csr, 16, 0.5)
+    c, _ = gpu_spmm(csr, perm, rg, 16, b)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "empty rows")
+    assert np.all(c[[0, 2, 4]] == 0.0)
+    dense = random_csr(rng, 48, 96, 1.0)
+    b = synth.dense_rhs(rng, 96, 128, "f16")
+    perm, rg = blocking_bit_exact(dense, 32, 0.5)
+    assert len(rg) == 2                                   # one group, three full blocks
+    c, _ = gpu_spmm(dense, perm, rg, 32, b)
+    a64 = oracle.bits_to_f64(synth.dense_bits(dense), "f16")
+    b64 = oracle.bits_to_f64(b, "f16")
+    check_c(c, a64 @ b64, np.abs(a64) @ np.abs(b64), "dense block vs numpy GEMM")
+
+
+def test_identity_like_right_hand_side_reproduces_rows_exactly():
+    rng = np.random.default_rng(8)
+    csr = random_csr(rng, 64, 64, 0.2)
+    eye = synth.to_bits(np.eye(64, dtype=np.float32), "f16")
+    perm, rg = blocking_bit_exact(csr, 16, 0.4)
+    c, _ = gpu_spmm(csr, perm, rg, 16, eye)
+    assert np.array_equal(c, oracle.bits_to_f64(synth.dense_bits(csr), "f16"))
+
+
+def test_argument_checks_on_the_gpu_entry():
+    import torch
+    rng = np.random.default_rng(9)
+    csr = random_csr(rng, 20, 32, 0.3)
+    perm, rg = binding.sa1_reorder(csr, 16, 0.5)
+    v = binding.vbr_build(csr, perm, rg, 16).upload("cuda:0")
+    b = torch.zeros((32, 16), dtype=torch.float16, device="cuda:0")
+    c = torch.zeros((20, 16), dtype=torch.float32, device="cuda:0")
+    s = torch.cuda.current_stream().cuda_stream
+    assert binding.vbr_spmm_raw(v, b.data_ptr(), 16, c.data_ptr(), 16, 12, s) == -1       # N % 8
+    assert binding.vbr_spmm_raw(v, b.data_ptr(), 8, c.data_ptr(), 16, 16, s) == -1        # ldb < N
+    assert binding.vbr_spmm_raw(v, b.data_ptr() + 2, 16, c.data_ptr(), 16, 16, s) == -1   # alignment
+    assert binding.vbr_spmm_raw(v, b.data_ptr(), 16, c.data_ptr(), 16, 0, s) == 0         # N = 0: nothing to do
+    assert binding.vbr_spmm_raw(v, b.data_ptr(), 16, c.data_ptr(), 16, 16, s) == 0
+    torch.cuda.synchronize()
+
+
+# --------------------------------------------------------------------------- the five workloads, reduced
+@pytest.mark.parametrize("name,scale,noise", [("c1", 1.0, True), ("c1", 1.0, False), ("c2", 0.25, True),
+                                               ("c2", 0.25, False), ("c3", 0.125, True), ("c4", 0.125, True),
+                                               ("c5", 0.0625, True)])
+def test_workloads_reduced_elementwise(name, scale, noise):
+    w = synth.workload(name, scale=scale, noise=noise)
+    c_ref, s = oracle.spmm(w["A"], w["B"])
+    for tau in w["taus"]:
+        perm, rg = blocking_bit_exact(w["A"], w["col_block"], tau)
+        c, v = gpu_spmm(w["A"], perm, rg, w["col_block"], w["B"])
+        index_bit_exact(v, w["A"], perm, rg, w["col_block"])
+        check_c(c, c_ref, s, "%s tau=%g" % (name, tau))
+
+
+# --------------------------------------------------------------------------- full sizes, sampled rows
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_workloads_full_size_sampled_rows(name):
+    w = synth.workload(name)
+    a, cb = w["A"], w["col_block"]
+    tau = w["taus"][len(w["taus"]) // 2]
+    perm, rg = blocking_bit_exact(a, cb, tau)
+    c, v = gpu_spmm(a, perm, rg, cb, w["B"])
+    index_bit_exact(v, a, perm, rg, cb)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([rng.integers(0, a["n_rows"], size=96),
+                                     perm[[0, -1]], [0, a["n_rows"] - 1]]))
+    c_ref, s = oracle.spmm(a, w["B"], rows=rows)
+    check_c(c[rows], c_ref, s, "%s full size, %d sampled rows" % (name, rows.size))
+    # property at any size: rows without entries are exactly zero, nothing is left unwritten
+    empty = np.nonzero(np.diff(a["row_ptr"]) == 0)[0]
+    assert not np.isnan(c).any() and np.all(c[empty] == 0.0)

@@ -1,0 +1,154 @@
+"""Host side of the C-ABI library against the oracle (CPU only, no GPU calls).
+
+sa1_reorder / vbr_build / vbr_get_index / vbr_unpack_block are host code inside the same shared
+library as the kernels; perm, row_groups and the VBR index arrays must match the oracle bit for
+bit.  Also: the library loads and exports every symbol the header declares, and the error paths.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2202_05868_amd import binding, synth
+from helpers import check_partition_shape, csr_from_rows, random_csr, sa1_sets
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+TAUS = [0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "vbr_spmm.h")).read()
+    declared = set(re.findall(r"^(?:const char \*|int64_t |int |void )\s*(\w+)\s*\(", header, flags=re.M))
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def assert_same_blocking(csr, col_block, tau):
+    p0, g0 = oracle.sa1(csr, col_block, tau)
+    p1, g1 = binding.sa1_reorder(csr, col_block, tau)
+    assert np.array_equal(p0, p1), "perm differs"
+    assert np.array_equal(g0, g1), "row_groups differ"
+    return p1, g1
+
+
+def assert_same_index(csr, perm, rg, col_block, check_values=True):
+    bp0, bc0, bo0 = oracle.vbr_index(csr, perm, rg, col_block)
+    v = binding.vbr_build(csr, perm, rg, col_block)
+    ix = v.index()
+    assert np.array_equal(ix["perm"], perm) and np.array_equal(ix["row_groups"], rg)
+    assert np.array_equal(ix["blk_ptr"], bp0)
+    assert np.array_equal(ix["blk_col"], bc0)
+    assert np.array_equal(ix["blk_off"], bo0)
+    assert ix["stored_elems"] == bo0[-1] and ix["n_blocks"] == len(bc0)
+    if check_values:
+        for g in range(len(rg) - 1):
+            h = int(rg[g + 1] - rg[g])
+            for b in range(int(bp0[g]), int(bp0[g + 1])):
+                got = v.unpack_block(b, h, col_block)
+                want = oracle.block_bits(csr, perm, rg, g, int(bc0[b]), col_block)
+                assert np.array_equal(got, want), (g, b)
+    return v
+
+
+@pytest.mark.parametrize("col_block", [1, 2, 3, 8, 16])
+def test_reorder_and_index_match_oracle_on_random_matrices(col_block):
+    rng = np.random.default_rng(100 + col_block)
+    for trial in range(12):
+        n_rows = int(rng.integers(1, 90))
+        kb = int(rng.integers(1, 20))
+        csr = random_csr(rng, n_rows, kb * col_block, float(rng.choice([0.02, 0.1, 0.3, 0.7])),
+                         dtype="bf16" if trial % 2 else "f16")
+        for tau in TAUS:
+            perm, rg = assert_same_blocking(csr, col_block, tau)
+            check_partition_shape(perm, rg, n_rows)
+        assert_same_index(csr, perm, rg, col_block)
+
+
+def test_reorder_matches_set_based_transcription_too():
+    rng = np.random.default_rng(9)
+    for trial in range(40):
+        csr = random_csr(rng, int(rng.integers(1, 12)), 12, 0.3)
+        for tau in TAUS:
+            p0, g0 = sa1_sets(csr, 2, tau)
+            p1, g1 = binding.sa1_reorder(csr, 2, tau)
+            assert np.array_equal(p0, p1) and np.array_equal(g0, g1)
+
+
+def test_more_than_64_column_blocks_and_hash_collisions():
+    # patterns {0,3} and {1,2} share the Eq. 5 hash (3) and the length: they must stay apart
+    csr = csr_from_rows([[0, 3], [1, 2], [0, 3], [1, 2], [0, 1, 2]], n_cols=4)
+    perm, rg = assert_same_blocking(csr, 1, 1.0)
+    assert len(rg) - 1 == 3
+    rng = np.random.default_rng(2)
+    csr = random_csr(rng, 300, 200 * 2, 0.03)        # 200 column blocks: bitsets of 4 words
+    for tau in (0.2, 0.5):
+        perm, rg = assert_same_blocking(csr, 2, tau)
+    assert_same_index(csr, perm, rg, 2)
+
+
+@pytest.mark.parametrize("name,scale,noise", [("c1", 1.0, True), ("c1", 1.0, False), ("c2", 0.25, True),
+                                               ("c3", 0.125, True), ("c4", 0.125, True), ("c5", 0.0625, True)])
+def test_workloads_small_scale_bit_exact(name, scale, noise):
+    w = synth.workload(name, scale=scale, noise=noise)
+    for tau in w["taus"]:
+        perm, rg = assert_same_blocking(w["A"], w["col_block"], tau)
+    v = assert_same_index(w["A"], perm, rg, w["col_block"], check_values=False)
+    # values: sampled blocks
+    ix = v.index()
+    rng = np.random.default_rng(0)
+    grp_of_blk = np.repeat(np.arange(ix["n_groups"]), np.diff(ix["blk_ptr"]))
+    for b in rng.choice(ix["n_blocks"], size=min(40, ix["n_blocks"]), replace=False):
+        g = int(grp_of_blk[b])
+        h = int(rg[g + 1] - rg[g])
+        assert np.array_equal(v.unpack_block(int(b), h, w["col_block"]),
+                              oracle.block_bits(w["A"], perm, rg, g, int(ix["blk_col"][b]), w["col_block"]))
+
+
+def test_build_accepts_any_valid_partition_and_tall_groups():
+    rng = np.random.default_rng(4)
+    csr = random_csr(rng, 300, 64, 0.1)
+    perm = rng.permutation(300).astype(np.int32)
+    rg = np.array([0, 1, 18, 150, 151, 300], dtype=np.int32)     # heights 1, 17, 132, 1, 149
+    assert_same_index(csr, perm, rg, 16)
+    assert_same_index(csr, np.arange(300, dtype=np.int32), np.array([0, 300], dtype=np.int32), 4)
+
+
+def test_empty_rows_and_empty_matrix():
+    csr = csr_from_rows([[], [1], [], [1, 5]], n_cols=8)
+    perm, rg = assert_same_blocking(csr, 2, 0.5)
+    assert_same_index(csr, perm, rg, 2)
+    empty = csr_from_rows([[], [], []], n_cols=8)
+    perm, rg = assert_same_blocking(empty, 4, 0.5)
+    assert len(rg) == 2
+    v = assert_same_index(empty, perm, rg, 4)
+    assert v.index()["n_blocks"] == 0 and v.device_bytes() >= 256
+
+
+def test_error_paths():
+    csr = csr_from_rows([[0, 1], [2]], n_cols=4)
+    with pytest.raises(binding.VbrError):
+        binding.sa1_reorder(csr, 3, 0.5)                 # 4 % 3 != 0
+    with pytest.raises(binding.VbrError):
+        binding.sa1_reorder(csr, 2, 1.5)                 # tau out of range
+    with pytest.raises(binding.VbrError):
+        binding.sa1_reorder(csr, 0, 0.5)
+    bad = dict(csr)
+    bad["col_idx"] = np.array([1, 0, 2], dtype=np.int32)  # unsorted inside a row
+    with pytest.raises(binding.VbrError):
+        binding.sa1_reorder(bad, 2, 0.5)
+    bad["col_idx"] = np.array([0, 1, 7], dtype=np.int32)  # out of range
+    with pytest.raises(binding.VbrError):
+        binding.sa1_reorder(bad, 2, 0.5)
+    with pytest.raises(binding.VbrError):
+        binding.vbr_build(csr, np.array([0, 0], dtype=np.int32), np.array([0, 2], dtype=np.int32), 2)  # not a bijection
+    with pytest.raises(binding.VbrError):
+        binding.vbr_build(csr, np.array([0, 1], dtype=np.int32), np.array([0, 1, 1, 2], dtype=np.int32), 2)  # empty group
+    v = binding.vbr_build(csr, np.array([1, 0], dtype=np.int32), np.array([0, 2], dtype=np.int32), 2)
+    # spmm before upload: state error, no GPU touched
+    assert binding.vbr_spmm_raw(v, 256, 8, 256, 8, 8, 0) == -4
+    assert binding._lib.vbr_strerror(-4) == b"call out of order"
