@@ -149,7 +149,8 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     for (int c = 0; c < 4; ++c) v->class_begin[c + 1] += v->class_begin[c];
 
     DeviceLayout &L = v->lay;
-    L.tiles_off = 0;
+    L.zeros_off = 0;                   // 256 zero bytes the kernel reads for padding
+    L.tiles_off = 256;
     L.krow_off = align_up(L.tiles_off + NT * (int64_t)sizeof(TileDesc), 256);
     L.perm_off = align_up(L.krow_off + (int64_t)v->krow.size() * 4, 256);
     L.vals_off = align_up(L.perm_off + M * 4, 256);

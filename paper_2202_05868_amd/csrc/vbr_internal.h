@@ -51,7 +51,7 @@ inline int64_t tile_kstep_stride(int32_t n_rows, int32_t n_slabs)
 
 // Byte offsets of the sections inside the device buffer (each 256-byte aligned).
 struct DeviceLayout {
-    int64_t tiles_off = 0, krow_off = 0, perm_off = 0, vals_off = 0, total = 0;
+    int64_t zeros_off = 0, tiles_off = 0, krow_off = 0, perm_off = 0, vals_off = 0, total = 0;
 };
 
 }  // namespace vbrk

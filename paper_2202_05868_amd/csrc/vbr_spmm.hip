@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "vbr_host.h"
 
@@ -19,8 +20,9 @@ namespace {
 constexpr int kThreads = 256;          // 4 waves
 constexpr int kTileN = 256;            // C columns per workgroup
 constexpr int kWaveN = 64;             // C columns per wave: 4 MFMA tiles of 16
-constexpr int kLdsRow = kTileN + 16;   // 16-bit values per staged B row; the 32-byte pad shifts
-                                       // consecutive rows by 8 LDS banks
+constexpr int kRowBytes = kTileN * 2;  // one staged B row in LDS: 512 bytes, no padding
+constexpr int kPanelBytes = kStepK * kRowBytes;   // 16 KiB of B per K-step
+constexpr int kFragBytes = kFragElems * 2;        // 1 KiB per A fragment
 constexpr int kXcd = 8;                // L2 domains; workgroup i runs on domain i % 8
 
 typedef short short4v __attribute__((ext_vector_type(4)));
@@ -29,12 +31,16 @@ typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+typedef __attribute__((address_space(3))) short8v *lds_short8_ptr;
+typedef __attribute__((address_space(3))) unsigned char *lds_u8_ptr;
+typedef __attribute__((address_space(4))) const int32_t *const_i32_ptr;
 
 struct Params {
     const TileDesc *tiles;    // tiles of this launch's slab class
     const int32_t *krow;
     const int32_t *perm;
     const uint16_t *vals;
+    const uint16_t *zeros;    // 256 zero bytes: source of padding rows, padding lanes and columns >= N
     const uint16_t *B;
     float *C;
     int64_t ldb, ldc;
@@ -53,12 +59,45 @@ __device__ __forceinline__ float4v mfma16x16x32(short8v a, short8v b, float4v c)
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8v, a), __builtin_bit_cast(bf16x8v, b), c, 0, 0, 0);
 }
 
-// S = slabs the instantiation computes (tiles of the class have S/2 < n_slabs <= S, n_slabs = 1 for S = 1).
-template <int DT, int S>
+// 16 bytes per active lane from global memory straight into LDS, no register staging: lane l's
+// data lands at lds_base + 16 l (lds_base wave-uniform, passed in M0).  The load is counted in
+// vmcnt like any vector load; the compiler does not see it, so the waits are placed by hand.
+// Every wave must issue the same, fixed number of these per K-step (never with an empty lane mask).
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+// same, address = wave-uniform base + zero-extended 32-bit lane offset
+__device__ __forceinline__ void dma16_base(uint32_t voff, const void *sbase, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// S  = slabs the instantiation computes (tiles of the class have S/2 < n_slabs <= S; 1 for S = 1).
+// NS = slots of the LDS ring of B panels: NS-1 K-steps of B loads are in flight per workgroup.
+// DA = prefetch distance of the A fragments in K-steps (ring of DA+1 slots): A is streamed from
+//      beyond L2 while B mostly hits in L2, and the loads of a wave retire in order.
+// The loop is bound by the instructions a wave needs per K-step, so the common case (block width a
+// multiple of 8, full column tile, no padding rows in the K-step) is kept to a handful of scalar
+// instructions per 1 KiB load; everything else takes the general path.
+template <int DT, int S, int NS, int DA>
 __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kStepK * kLdsRow];
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][S * kFragElems];
+    static_assert(NS >= 2 && DA >= NS - 1, "A must be requested before the B panel of its K-step");
+    constexpr int NA = S >= 4 ? S / 4 : 1;      // A loads per wave per K-step
+    constexpr int NAS = DA + 1;
+    constexpr int kAStage = S * kFragBytes;
+    constexpr int kBRing = NS * kPanelBytes;
+    // loads younger than the last B load of K-step ks when the workgroup waits for it
+    constexpr int kWait = (NS - 2) * 4 + (NS - 1) * NA;
+    static_assert(kWait < 64, "vmcnt is a 6-bit counter");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kBRing + NAS * kAStage];
 
     // Workgroup -> (tile, column tile).  Workgroups are dealt to the 8 L2 domains round-robin;
     // a domain keeps to few column tiles so that the B columns it gathers stay in its L2.
@@ -76,26 +115,14 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
         if (tile >= T) return;
     }
     const TileDesc td = p.tiles[tile];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = ntile * kTileN;
-
-    // staging role for B: 16-byte column chunk bc of rows br, br+8, br+16, br+24 of the K-step
-    const int bc = tid & 31, br = tid >> 5;
-    const bool col_ok = n0 + bc * 8 < p.N;
-    const uint16_t *Bcol = p.B + n0 + bc * 8;
-    const int gmask = (1 << p.lg_gran) - 1;
-    // staging role for A: fragment lane `lane` of slabs wave, wave+4
-    constexpr int NA = (S + 3) / 4;
-    const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
-    const int64_t a_stride = (int64_t)(td.n_slabs - 1) * kFragElems + (int64_t)rows_last * kStepK;
-    const uint16_t *Abase = p.vals + td.a_off * 8;
-    int a_src[NA];      // offset of this thread's 16 bytes inside a K-step of the tile, -1 = padding
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int s = wave + 4 * i, m = lane & 15, q = lane >> 4;
-        const int rows = (s == td.n_slabs - 1) ? rows_last : kSlabRows;
-        a_src[i] = (s < td.n_slabs && s < S && m < rows) ? s * kFragElems + (q * rows + m) * 8 : -1;
-    }
+    const lds_u8_ptr sm = (lds_u8_ptr)(&smem[0]);
+    const uint32_t smem_base = (uint32_t)(uintptr_t)sm;      // LDS byte address, for M0
+    const char *zeros = reinterpret_cast<const char *>(p.zeros);
+    const int n_ks = td.n_ks;
+    const int q = lane >> 4, s16 = lane & 15;
 
     float4v acc[S][4];
 #pragma unroll
@@ -103,76 +130,147 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
 #pragma unroll
         for (int f = 0; f < 4; ++f) acc[s][f] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    int rowidx[4];
-    uint4 breg[4], areg[NA];
-    auto load_rows = [&](int ks) {
+    if (n_ks > 0) {
+        // ---- B staging.  Per K-step a wave issues 4 loads; load i brings rows 8 wave + 2 i (lanes
+        // 0-31) and 8 wave + 2 i + 1 (lanes 32-63) of the K-step, 512 bytes each, into 1 KiB of LDS.
+        // LDS chunk c' (16 bytes) of row r holds global chunk c' ^ 2 (r % 8): the XOR spreads the
+        // four rows one transposed read touches over distinct banks (rows are 512 bytes apart).
+        const int half = lane >> 5;
+        const int lg = p.lg_gran;
+        const int gmask = (1 << lg) - 1;
+        const const_i32_ptr krow = (const_i32_ptr)p.krow + (int64_t)td.ks_begin * (kStepK >> lg);
+        const uint32_t ldb_bytes = (uint32_t)(p.ldb * 2);          // host checked: K * ldb * 2 < 2^32
+        const char *Btile = reinterpret_cast<const char *>(p.B) + (int64_t)n0 * 2;
+        const bool tile_fast = lg >= 3 && n0 + kTileN <= p.N;
+        uint32_t b_col[4];       // byte offset of this lane's chunk from the tile's first column
+        uint32_t b_lane[4];      // fast path: offset of this lane's 16 bytes from the first row of the wave's granule
+        bool b_col_ok[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = br + 8 * i;
-            const int base = p.krow[((td.ks_begin + ks) * kStepK + r) >> p.lg_gran];
-            rowidx[i] = base < 0 ? -1 : base + (r & gmask);
+            const int chunk = (lane & 31) ^ (2 * (2 * i + half));
+            b_col[i] = chunk * 16;
+            b_col_ok[i] = n0 + chunk * 8 < p.N;
+            b_lane[i] = (uint32_t)((8 * wave + 2 * i + half) & gmask) * ldb_bytes + b_col[i];
         }
-    };
-    auto load_tiles = [&](int ks) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            breg[i] = uint4{0u, 0u, 0u, 0u};
-            if (rowidx[i] >= 0 && col_ok) breg[i] = *reinterpret_cast<const uint4 *>(Bcol + (int64_t)rowidx[i] * p.ldb);
-        }
+
+        // ---- A staging: every wave issues NA loads per K-step, each a lane range of one fragment.
+        // Lanes of rows a partial last slab does not store are masked off (their LDS bytes keep
+        // whatever they held: those fragment rows only feed C rows that are never stored); a wave
+        // whose slab does not exist in this tile reloads the tile's last slab instead, so that the
+        // number of loads per wave stays fixed and no load has an empty lane mask.
+        const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
+        const uint32_t a_stride_bytes = (uint32_t)(((td.n_slabs - 1) * kFragElems + rows_last * kStepK) * 2);
+        const char *Abase = reinterpret_cast<const char *>(p.vals) + td.a_off * 16;
+        int a_slab[NA];
+        uint32_t a_lane[NA];     // byte offset of this lane's 16 bytes inside a K-step of the tile
+        bool a_on[NA];
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            areg[i] = uint4{0u, 0u, 0u, 0u};
-            if (a_src[i] >= 0) areg[i] = *reinterpret_cast<const uint4 *>(Abase + (int64_t)ks * a_stride + a_src[i]);
+            bool part;           // lanes of the fragment this wave loads
+            if constexpr (S == 1) { a_slab[i] = 0; part = q == wave; }
+            else if constexpr (S == 2) { a_slab[i] = wave & 1; part = (lane >> 5) == (wave >> 1); }
+            else { a_slab[i] = wave + 4 * i; part = true; }
+            if (a_slab[i] > td.n_slabs - 1) a_slab[i] = td.n_slabs - 1;
+            const int rows = (a_slab[i] == td.n_slabs - 1) ? rows_last : kSlabRows;
+            a_on[i] = part && s16 < rows;
+            a_lane[i] = (uint32_t)((a_slab[i] * kFragElems + (q * rows + s16) * 8) * 2);
         }
-    };
-    auto store_tiles = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4 *>(&Bs[buf][(br + 8 * i) * kLdsRow + bc * 8]) = breg[i];
-#pragma unroll
-        for (int i = 0; i < NA; ++i)
-            if (wave + 4 * i < S) *reinterpret_cast<uint4 *>(&As[buf][(wave + 4 * i) * kFragElems + lane * 8]) = areg[i];
-    };
 
-    const int n_ks = td.n_ks;
-    if (n_ks > 0) {
-        load_rows(0);
-        load_tiles(0);
-        if (n_ks > 1) load_rows(1);
-        store_tiles(0);
-    }
-    __syncthreads();
+        // First B row of the granule holding this wave's 8 rows (blocks at least 8 wide), for the
+        // K-step whose B loads are issued next (rb0) and the one after (rb1): scalar loads, issued
+        // two iterations ahead of their use.  Narrower blocks look their rows up per lane at issue
+        // time instead, with an ordinary load the compiler waits for (slow, but rare and simple).
+        int rb0 = -1, rb1 = -1;
+        auto load_rows = [&](int ks) -> int {
+            const int kc = ks < n_ks ? ks : n_ks - 1;      // past the end: reload the last K-step (never computed)
+            return lg >= 3 ? krow[(kc * kStepK + 8 * wave) >> lg] : -1;
+        };
+        auto issue_b = [&](int ks, int slot) {
+            const uint32_t sb = smem_base + slot * kPanelBytes + 8 * wave * kRowBytes;
+            if (tile_fast && rb0 >= 0) {
+                const char *rowptr = Btile + (uint32_t)rb0 * ldb_bytes;          // scalar
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dma16_base(b_lane[i], rowptr, sb + 2 * i * kRowBytes);
+            } else {         // narrow blocks, padding rows or column tail: zeros come from the zero page
+                const int kc = ks < n_ks ? ks : n_ks - 1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 8 * wave + 2 * i + half;
+                    const int e = lg >= 3 ? rb0 : p.krow[(int64_t)td.ks_begin * (kStepK >> lg) + ((kc * kStepK + r) >> lg)];
+                    const char *src = (e >= 0 && b_col_ok[i]) ? Btile + (int64_t)(e + (r & gmask)) * ldb_bytes + b_col[i] : zeros;
+                    dma16(src, sb + 2 * i * kRowBytes);
+                }
+            }
+        };
+        auto issue_a = [&](int ks, int slot) {
+            const int kc = ks < n_ks ? ks : n_ks - 1;
+            const char *kptr = Abase + (int64_t)kc * a_stride_bytes;             // scalar
+            const uint32_t sa = smem_base + kBRing + slot * kAStage;
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                if (a_on[i]) dma16_base(a_lane[i], kptr, sa + a_slab[i] * kFragBytes);
+        };
 
-    // B fragment of MFMA tile f, half r: lane (q, s16) reads 4 values of B row
-    // 8 (2 (q/2) + r) + 4 (q%2) + s16/4 at column 64 wave + 16 f + 4 (s16 % 4); the transposed
-    // read hands every lane the 4 rows of ITS column (column s16 of the tile).
-    const int q = lane >> 4, s16 = lane & 15;
-    const int b_base = (16 * (q >> 1) + 4 * (q & 1) + (s16 >> 2)) * kLdsRow + wave * kWaveN + 4 * (s16 & 3);
+        // B fragment of MFMA tile f, half r: lane (q, s16) reads 8 bytes of B row
+        // R = 16 (q/2) + 8 r + 4 (q%2) + s16/4 at columns 64 wave + 16 f + 4 (s16%4) ..+3; the
+        // transposed read hands every lane the 4 rows of ITS column (column s16 of the tile).
+        uint32_t b_off[4];
+        {
+            const int R0 = 16 * (q >> 1) + 4 * (q & 1) + (s16 >> 2);       // r adds 8 rows: R % 8 unchanged
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const int chunk = 8 * wave + 2 * f + ((s16 & 3) >> 1);
+                b_off[f] = R0 * kRowBytes + ((chunk ^ (2 * (R0 & 7))) << 4) + (s16 & 1) * 8;
+            }
+        }
+        auto compute = [&](int bslot, int aslot) {
+            const lds_u8_ptr sb = sm + bslot * kPanelBytes;
+            const lds_u8_ptr sa = sm + kBRing + aslot * kAStage;
+            short8v bfrag[4];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sb + b_off[f]));
+                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sb + b_off[f] + 8 * kRowBytes));
+                bfrag[f] = short8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const short8v afrag = *(lds_short8_ptr)(sa + s * kFragBytes + lane * 16);
+                // operands swapped: the result tile comes out transposed, so a lane holds 4
+                // consecutive columns of one C row and stores them as one 16-byte word
+#pragma unroll
+                for (int f = 0; f < 4; ++f) acc[s][f] = mfma16x16x32<DT>(bfrag[f], afrag, acc[s][f]);
+            }
+        };
 
-    for (int ks = 0; ks < n_ks; ++ks) {
-        const int cur = ks & 1;
-        const bool more = ks + 1 < n_ks;
-        if (more) {
-            load_tiles(ks + 1);
-            if (ks + 2 < n_ks) load_rows(ks + 2);
-        }
-        short8v bfrag[4];
+        // ---- software pipeline over the K-steps.  Issue order, as if the loop had started NS-1
+        // iterations early: A(0 .. DA-NS), then B(t), A(DA-NS+1+t) for t = 0 .. NS-2; iteration ks
+        // then issues B(ks+NS-1), A(ks+DA).  K-steps past the end re-load the last one, so that the
+        // number of loads in flight, which the vmcnt wait relies on, never changes.
+        rb0 = load_rows(0);
+        rb1 = load_rows(1);
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(&Bs[cur][b_base + 16 * f]));
-            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(&Bs[cur][b_base + 16 * f + 8 * kLdsRow]));
-            bfrag[f] = short8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        }
+        for (int k = 0; k <= DA - NS; ++k) issue_a(k, k);
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            const short8v afrag = *reinterpret_cast<const short8v *>(&As[cur][s * kFragElems + lane * 8]);
-            // operands swapped: the result tile comes out transposed, so a lane holds 4 consecutive
-            // columns of one C row and stores them as one 16-byte word
-#pragma unroll
-            for (int f = 0; f < 4; ++f) acc[s][f] = mfma16x16x32<DT>(bfrag[f], afrag, acc[s][f]);
+        for (int t = 0; t < NS - 1; ++t) {
+            issue_b(t, t);
+            rb0 = rb1;
+            rb1 = load_rows(t + 2);
+            issue_a(DA - NS + 1 + t, DA - NS + 1 + t);
         }
-        if (more) store_tiles(cur ^ 1);
-        __syncthreads();
+        int bslot = 0, aslot = 0;
+        for (int ks = 0; ks < n_ks; ++ks) {
+            wait_vmcnt<kWait>();                   // this wave's loads of K-step ks have landed
+            __builtin_amdgcn_s_barrier();          // ... and everybody else's; the slots of K-step ks-1 are free
+            issue_b(ks + NS - 1, bslot == 0 ? NS - 1 : bslot - 1);
+            rb0 = rb1;
+            rb1 = load_rows(ks + NS + 1);
+            issue_a(ks + DA, aslot == 0 ? NAS - 1 : aslot - 1);
+            compute(bslot, aslot);
+            bslot = bslot == NS - 1 ? 0 : bslot + 1;
+            aslot = aslot == NAS - 1 ? 0 : aslot + 1;
+        }
+        wait_vmcnt<0>();                           // no load may still be writing LDS when the workgroup ends
     }
 
     // C rows go back to their original positions through perm; beta = 0
@@ -191,6 +289,10 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
     }
 }
 
+constexpr int kStages = 3;     // LDS ring of B panels
+
+template <int S> constexpr int a_distance() { return S == 1 ? 11 : S == 2 ? 7 : S == 4 ? 5 : 3; }
+
 template <int DT, int S>
 int launch_class(const vbr *v, const Params &base, int cls, hipStream_t stream)
 {
@@ -204,7 +306,7 @@ int launch_class(const vbr *v, const Params &base, int cls, hipStream_t stream)
     if (Q >= kXcd) grid = (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
     else grid = (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
     if (grid > INT32_MAX) return VBR_EINVAL;
-    hipLaunchKernelGGL((vbr_spmm_kernel<DT, S>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((vbr_spmm_kernel<DT, S, kStages, a_distance<S>()>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
     return VBR_OK;
@@ -232,7 +334,9 @@ extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
     char *d = static_cast<char *>(buf_dev);
     const vbrk::DeviceLayout &L = v->lay;
     struct Part { int64_t off; const void *src; size_t bytes; };
-    const Part parts[4] = {
+    static const unsigned char kZeros[256] = {0};
+    const Part parts[5] = {
+        {L.zeros_off, kZeros, sizeof(kZeros)},
         {L.tiles_off, v->tiles.data(), v->tiles.size() * sizeof(vbrk::TileDesc)},
         {L.krow_off, v->krow.data(), v->krow.size() * 4},
         {L.perm_off, v->perm.data(), v->perm.size() * 4},
@@ -257,6 +361,7 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     if (N < 0 || N % 8 != 0 || N > (int64_t)INT32_MAX - 1024) return VBR_EINVAL;
     if (N == 0 || v->n_rows == 0) return VBR_OK;
     if (!B_dev || !C_dev || ldb < N || ldc < N || ldb % 8 != 0 || ldc % 4 != 0) return VBR_EINVAL;
+    if (v->n_cols * ldb * 2 >= ((int64_t)1 << 32)) return VBR_EUNSUPPORTED;   // B rows are addressed with 32-bit byte offsets
     if ((reinterpret_cast<uintptr_t>(B_dev) & 15) != 0 || (reinterpret_cast<uintptr_t>(C_dev) & 15) != 0) return VBR_EINVAL;
     const char *d = static_cast<const char *>(v->dev);
     vbrk::Params p;
@@ -264,6 +369,7 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     p.krow = reinterpret_cast<const int32_t *>(d + v->lay.krow_off);
     p.perm = reinterpret_cast<const int32_t *>(d + v->lay.perm_off);
     p.vals = reinterpret_cast<const uint16_t *>(d + v->lay.vals_off);
+    p.zeros = reinterpret_cast<const uint16_t *>(d + v->lay.zeros_off);
     p.B = static_cast<const uint16_t *>(B_dev);
     p.C = C_dev;
     p.ldb = ldb;
