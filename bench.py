@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--clean", action="store_true", help="noise-free variant of c1/c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB streaming kernel, out = 2*in (outside the timed region): the known-size "
+                         "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (row groups shard "
@@ -78,6 +81,14 @@ def main() -> int:
 
     b = torch_io.bits_to_device(w["B"], w["dtype"], dev)
     c = torch.empty((a["n_rows"], n), dtype=torch.float32, device=dev)
+
+    if args.calib_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 2.0, out=dst)       # one streaming elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: K launches between HIP events on the launch stream
     stream = torch.cuda.current_stream()

@@ -1,8 +1,8 @@
 // vbr_spmm on gfx950: C = A.B with A in packed VBR form (section 4.4.1 of the paper: every stored
 // block is multiplied as a dense product on the matrix units).  One launch per slab class; each
 // workgroup owns up to 8 slabs of 16 rows of ONE row group and a 256-column tile of C, walks the
-// group's block list in K-steps of 32 B rows, stages the gathered B rows and the A fragments in
-// LDS (double buffered, 128-bit global loads), and issues v_mfma_f32_16x16x32 on them.
+// group's block list in K-steps of 32 B rows, brings the gathered B rows and the A fragments into
+// rings of LDS slots with 128-bit direct-to-LDS loads, and issues v_mfma_f32_16x16x32 on them.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -65,12 +65,18 @@ __device__ __forceinline__ float4v mfma16x16x32(short8v a, short8v b, float4v c)
 // Every wave must issue the same, fixed number of these per K-step (never with an empty lane mask).
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr),
+                 "s"((uint32_t)__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
 }
 // same, address = wave-uniform base + zero-extended 32-bit lane offset
-__device__ __forceinline__ void dma16_base(uint32_t voff, const void *sbase, uint32_t lds_base)
+__device__ __forceinline__ void dma16_base(uint32_t voff, const void *base, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+    // the base has to sit in scalar registers: say so explicitly (a no-op when it already does)
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    const uint64_t sbase = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32) |
+                           (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase),
+                 "s"((uint32_t)__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
 }
 
 template <int N>
@@ -289,9 +295,12 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
     }
 }
 
-constexpr int kStages = 3;     // LDS ring of B panels
+// Measured on the 16-row workload: two ring slots and four resident workgroups per CU (36 KiB of
+// LDS each) beat deeper rings with fewer workgroups; the gather is bound by how many independent
+// instruction streams feed the texture-address unit, not by the depth of any one of them.
+constexpr int kStages = 2;      // LDS ring of B panels
 
-template <int S> constexpr int a_distance() { return S == 1 ? 11 : S == 2 ? 7 : S == 4 ? 5 : 3; }
+constexpr int kADistance = 3;   // K-steps the A fragments are requested ahead
 
 template <int DT, int S>
 int launch_class(const vbr *v, const Params &base, int cls, hipStream_t stream)
@@ -306,7 +315,7 @@ int launch_class(const vbr *v, const Params &base, int cls, hipStream_t stream)
     if (Q >= kXcd) grid = (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
     else grid = (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
     if (grid > INT32_MAX) return VBR_EINVAL;
-    hipLaunchKernelGGL((vbr_spmm_kernel<DT, S, kStages, a_distance<S>()>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((vbr_spmm_kernel<DT, S, kStages, kADistance>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
     return VBR_OK;
