@@ -18,6 +18,13 @@ inline int slab_class(int n_slabs)   // kernels exist for 1, 2, 4 and 8 slabs
     return n_slabs <= 1 ? 0 : n_slabs <= 2 ? 1 : n_slabs <= 4 ? 2 : 3;
 }
 
+// Rows of groups shorter than a slab go into panels when the block width allows the scalar
+// gather path and there are enough of them to give every CU a panel or two (a panel is one long
+// running workgroup per 128 columns; a handful of them would leave most of the chip idle).
+constexpr int kPanelSlabs = 16;
+constexpr int64_t kPanelMinRows = 4096;
+inline bool use_panels(int lg_gran, int64_t short_rows) { return lg_gran >= 3 && short_rows >= kPanelMinRows; }
+
 int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups, int32_t G,
                int32_t col_block, vbr *v)
 {
@@ -39,17 +46,23 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     v->lg_gran = lg;
     const int gran = 1 << lg;
     const int per_step = kStepK >> lg;   // krow entries per K-step
+    int64_t short_rows = 0;
+    for (int32_t g = 0; g < G; ++g)
+        if (row_groups[g + 1] - row_groups[g] < kSlabRows) short_rows += row_groups[g + 1] - row_groups[g];
+    const bool panels_on = use_panels(lg, short_rows);
 
     v->blk_ptr.assign((size_t)G + 1, 0);
     v->blk_off.assign(1, 0);
     v->ks_ptr.assign((size_t)G + 1, 0);
     v->group_first_tile.assign((size_t)G + 1, 0);
+    v->group_prow.assign((size_t)std::max<int32_t>(G, 1), -1);
     std::vector<int32_t> pos_of_block((size_t)std::max<int64_t>(KB, 1), -1);
     std::vector<int32_t> blocks;
     std::vector<TileDesc> tiles;
     int64_t a_units = 0;   // running size of the packed values, in units of 8 values
 
-    // pass 1: index arrays, K-step gather lists, tiles
+    // pass 1: the VBR index arrays; K-step gather lists and tiles of the tall groups; the row list
+    // of the short groups
     for (int32_t g = 0; g < G; ++g) {
         const int64_t r0 = row_groups[g], r1 = row_groups[g + 1];
         const int64_t h = r1 - r0;
@@ -73,6 +86,14 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             v->blk_off.push_back(v->blk_off.back() + h * col_block);
         }
         v->blk_ptr[g + 1] = v->blk_ptr[g] + nb;
+        v->ks_ptr[g + 1] = v->ks_ptr[g];
+        v->group_first_tile[g + 1] = v->group_first_tile[g];
+
+        if (panels_on && h < kSlabRows) {           // short group: its rows join the panel region
+            v->group_prow[g] = (int32_t)v->prow.size();
+            for (int64_t q = r0; q < r1; ++q) v->prow.push_back(perm[q]);
+            continue;
+        }
 
         const int64_t Kg = nb * col_block;
         const int64_t n_ks = (Kg + kStepK - 1) / kStepK;
@@ -104,10 +125,107 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         }
     }
 
-    // pass 2: values into fragments
-    v->vals.assign((size_t)a_units * 8, 0);
+    // pass 2: panels.  Slabs are cut from the short rows in order; a panel walks the union of the
+    // column blocks of the groups its rows belong to.
+    const int64_t n_prows = (int64_t)v->prow.size();
+    std::vector<int32_t> prow_group((size_t)n_prows);
+    for (int32_t g = 0; g < G; ++g)
+        if (v->group_prow[g] >= 0)
+            for (int64_t i = 0; i < row_groups[g + 1] - row_groups[g]; ++i) prow_group[v->group_prow[g] + i] = g;
+    const int R = kPanelSlabs;
+    v->panel_slabs = n_prows > 0 ? R : 0;
+    const int max_frags = kPanelMaxFrags;
+    const int64_t panel_rows = (int64_t)R * kSlabRows;
+    const int64_t n_panels = (n_prows + panel_rows - 1) / panel_rows;
+    v->p_union_ptr.assign(1, 0);
+    std::vector<uint32_t> blk_mask;            // per union block: slabs that store it
+    std::vector<int64_t> frag_of;              // [logical step][slab] -> fragment ordinal in the panel, -1
+    const int64_t tiles_units = a_units;       // panels' values follow the tiles'
+    for (int64_t pn = 0; pn < n_panels; ++pn) {
+        const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
+        // union of blocks, and per block the slabs that hold it
+        blocks.clear();
+        for (int64_t i = i0; i < i1; ++i) {
+            const int32_t g = prow_group[i];
+            if (i > i0 && prow_group[i - 1] == g) continue;
+            for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b)
+                if (pos_of_block[v->blk_col[b]] < 0) { pos_of_block[v->blk_col[b]] = 0; blocks.push_back(v->blk_col[b]); }
+        }
+        std::sort(blocks.begin(), blocks.end());
+        const int64_t nu = (int64_t)blocks.size();
+        for (int64_t u = 0; u < nu; ++u) pos_of_block[blocks[u]] = (int32_t)u;
+        blk_mask.assign((size_t)nu, 0u);
+        for (int64_t i = i0; i < i1; ++i) {
+            const int32_t g = prow_group[i];
+            const uint32_t bit = 1u << ((i - i0) / kSlabRows);
+            for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) blk_mask[pos_of_block[v->blk_col[b]]] |= bit;
+        }
+        v->p_union.insert(v->p_union.end(), blocks.begin(), blocks.end());
+        v->p_union_ptr.push_back((int64_t)v->p_union.size());
+
+        PanelDesc pd;
+        pd.ks_begin = (int32_t)v->pk_mask.size();
+        pd.a_off = a_units;
+        pd.row_begin = (int32_t)i0;
+        pd.n_rows = (int32_t)(i1 - i0);
+        pd.pad = 0;
+        pd.meta_begin = (int32_t)(v->pk_meta.size() / (size_t)(1 + per_step));
+        const int64_t Ku = nu * col_block;
+        const int64_t T = (Ku + kStepK - 1) / kStepK;
+        frag_of.assign((size_t)(T * R), -1);
+        int64_t n_frags = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            uint32_t m = 0;
+            for (int64_t u = (t * kStepK) / col_block; u <= std::min(nu - 1, (t * kStepK + kStepK - 1) / col_block); ++u) m |= blk_mask[u];
+            // a physical K-step carries at most max_frags fragments: split the rest into repeats
+            while (m != 0) {
+                uint32_t part = 0;
+                int cnt = 0;
+                for (int s = 0; s < R && cnt < max_frags; ++s)
+                    if (m >> s & 1) { part |= 1u << s; frag_of[(size_t)(t * R + s)] = n_frags + cnt; ++cnt; }
+                m &= ~part;
+                v->pk_mask.push_back(part);
+                v->pk_logical.push_back((int32_t)t);
+                v->pk_frag.push_back(n_frags);
+                n_frags += cnt;
+                for (int e = 0; e < per_step; ++e) {
+                    const int64_t k = t * kStepK + (int64_t)e * gran;
+                    v->pk_row.push_back(k < Ku ? (int32_t)((int64_t)blocks[k / col_block] * col_block + k % col_block) : -1);
+                }
+            }
+        }
+        pd.n_ks = (int32_t)v->pk_mask.size() - pd.ks_begin;
+        if ((int64_t)v->pk_mask.size() > INT32_MAX / 64) return VBR_EINVAL;
+        // the device's K-step stream: one record per physical step, then the look-ahead padding
+        for (int64_t ph = pd.ks_begin; ph < pd.ks_begin + pd.n_ks + (pd.n_ks > 0 ? kPanelMetaPad : 0); ++ph) {
+            const int64_t src_ph = std::min<int64_t>(ph, pd.ks_begin + pd.n_ks - 1);
+            v->pk_meta.push_back(ph < pd.ks_begin + pd.n_ks ? (int32_t)v->pk_mask[ph] : 0);
+            for (int e = 0; e < per_step; ++e) v->pk_meta.push_back(v->pk_row[(size_t)src_ph * per_step + e]);
+        }
+        // values: one full 16 x 32 fragment per (physical step, present slab)
+        v->vals.resize((size_t)(a_units + n_frags * (kFragElems / 8)) * 8, 0);
+        const uint16_t *src = static_cast<const uint16_t *>(csr->vals);
+        uint16_t *dst = &v->vals[(size_t)a_units * 8];
+        for (int64_t i = i0; i < i1; ++i) {
+            const int64_t r = v->prow[i];
+            const int s = (int)((i - i0) / kSlabRows), mrow = (int)((i - i0) % kSlabRows);
+            for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                const int64_t c = csr->col_idx[p];
+                const int64_t k = (int64_t)pos_of_block[c / col_block] * col_block + c % col_block;
+                dst[frag_of[(size_t)((k / kStepK) * R + s)] * kFragElems + frag_index(mrow, (int)(k % kStepK), kSlabRows)] = src[p];
+            }
+        }
+        a_units += n_frags * (kFragElems / 8);
+        for (int64_t u = 0; u < nu; ++u) pos_of_block[blocks[u]] = -1;
+        v->panels.push_back(pd);
+    }
+
+    // pass 3: values of the tiles into fragments (the tiles' region precedes the panels')
+    if (v->vals.size() < (size_t)a_units * 8) v->vals.resize((size_t)a_units * 8, 0);
+    (void)tiles_units;
     const uint16_t *src = static_cast<const uint16_t *>(csr->vals);
     for (int32_t g = 0; g < G; ++g) {
+        if (v->group_first_tile[g] == v->group_first_tile[g + 1]) continue;
         for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) pos_of_block[v->blk_col[b]] = (int32_t)(b - v->blk_ptr[g]);
         for (int64_t t = v->group_first_tile[g]; t < v->group_first_tile[g + 1]; ++t) {
             const TileDesc &td = tiles[t];
@@ -127,6 +245,8 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         }
         for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) pos_of_block[v->blk_col[b]] = -1;
     }
+    // one fragment of zeros behind the last value: loads that run past a panel's data stay inside
+    v->vals.resize(v->vals.size() + kFragElems, 0);
 
     // schedule: tiles grouped by slab class (one kernel instantiation each), heaviest first
     const int64_t NT = (int64_t)tiles.size();
@@ -153,7 +273,10 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     L.tiles_off = 256;
     L.krow_off = align_up(L.tiles_off + NT * (int64_t)sizeof(TileDesc), 256);
     L.perm_off = align_up(L.krow_off + (int64_t)v->krow.size() * 4, 256);
-    L.vals_off = align_up(L.perm_off + M * 4, 256);
+    L.panels_off = align_up(L.perm_off + M * 4, 256);
+    L.pk_meta_off = align_up(L.panels_off + (int64_t)v->panels.size() * (int64_t)sizeof(PanelDesc), 256);
+    L.prow_off = align_up(L.pk_meta_off + (int64_t)v->pk_meta.size() * 4, 256);
+    L.vals_off = align_up(L.prow_off + n_prows * 4, 256);
     L.total = std::max<int64_t>(256, align_up(L.vals_off + (int64_t)v->vals.size() * 2, 256));
     return VBR_OK;
 }
@@ -217,6 +340,32 @@ extern "C" int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst_)
     const int64_t pos = blk - v->blk_ptr[g];
     const int64_t cb = v->col_block;
     uint16_t *dst = static_cast<uint16_t *>(dst_);
+    if (v->group_prow[g] >= 0) {
+        // short group: its rows sit in a panel (or two); find the fragments through the panel's union
+        const int64_t h = v->row_groups[g + 1] - v->row_groups[g];
+        const int R = v->panel_slabs;
+        const int64_t panel_rows = (int64_t)R * kSlabRows;
+        for (int64_t i = 0; i < h; ++i) {
+            const int64_t pi = v->group_prow[g] + i;
+            const int64_t pn = pi / panel_rows;
+            const PanelDesc &pd = v->panels[pn];
+            const int s = (int)((pi - pd.row_begin) / kSlabRows), m = (int)((pi - pd.row_begin) % kSlabRows);
+            const int32_t *ub = &v->p_union[v->p_union_ptr[pn]], *ue = &v->p_union[0] + v->p_union_ptr[pn + 1];
+            const int64_t u = std::lower_bound(ub, ue, v->blk_col[blk]) - ub;
+            for (int64_t c = 0; c < cb; ++c) {
+                const int64_t k = u * cb + c;
+                const int32_t t = (int32_t)(k / kStepK);
+                // physical steps of logical step t are consecutive; take the one that carries slab s
+                const int32_t *lb = &v->pk_logical[pd.ks_begin], *le = lb + pd.n_ks;
+                int64_t ph = pd.ks_begin + (std::lower_bound(lb, le, t) - lb);
+                while (!(v->pk_mask[ph] >> s & 1)) ++ph;
+                const int rank = __builtin_popcount(v->pk_mask[ph] & ((1u << s) - 1u));
+                dst[i * cb + c] = v->vals[(size_t)pd.a_off * 8 + (size_t)(v->pk_frag[ph] + rank) * kFragElems +
+                                          frag_index(m, (int)(k % kStepK), kSlabRows)];
+            }
+        }
+        return VBR_OK;
+    }
     int64_t row = 0;
     for (int64_t t = v->group_first_tile[g]; t < v->group_first_tile[g + 1]; ++t) {
         const TileDesc &td = v->tiles[v->tile_of_group_order[t]];
@@ -240,8 +389,8 @@ extern "C" int64_t vbr_device_bytes(const vbr_t *v) { return v ? v->lay.total : 
 extern "C" int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems)
 {
     if (!v) return VBR_EINVAL;
-    if (n_tiles) *n_tiles = (int64_t)v->tiles.size();
-    if (n_ksteps) *n_ksteps = v->ks_ptr.back();
+    if (n_tiles) *n_tiles = (int64_t)v->tiles.size() + (int64_t)v->panels.size();
+    if (n_ksteps) *n_ksteps = v->ks_ptr.back() + (int64_t)v->pk_mask.size();
     if (packed_elems) *packed_elems = (int64_t)v->vals.size();
     return VBR_OK;
 }

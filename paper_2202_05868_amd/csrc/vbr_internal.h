@@ -49,9 +49,28 @@ inline int64_t tile_kstep_stride(int32_t n_rows, int32_t n_slabs)
     return (int64_t)(n_slabs - 1) * kFragElems + (int64_t)rows_last * kStepK;
 }
 
+// One workgroup panel: up to 32 slabs cut from the rows of SHORT row groups (height < 16) in
+// permuted order, whatever group they belong to, walked over the union of the column blocks of
+// those groups.  A B row panel is loaded once per K-step for all slabs; a slab only multiplies
+// where its own groups store a block (mask bit), its fragment then follows in the value stream.
+struct PanelDesc {
+    int32_t ks_begin;    // first physical K-step of the panel (index into the host's pk_mask / pk_row)
+    int32_t n_ks;        // physical K-steps
+    int64_t a_off;       // first value of the panel, in units of 8 values (16 bytes)
+    int32_t row_begin;   // first row of the panel in the panel-row list
+    int32_t n_rows;      // rows of the panel, 1 .. 16 * slabs per panel
+    int32_t meta_begin;  // first record of the panel in the device's K-step stream (pk_meta)
+    int32_t pad;
+};
+static_assert(sizeof(PanelDesc) == 32, "PanelDesc is read by the kernel as 2 x 16 bytes");
+
+constexpr int kPanelMaxFrags = 8;    // fragments per physical K-step (one load per wave); more -> the step is split
+constexpr int kPanelMetaPad = 12;    // records appended to a panel's K-step stream, so that the kernel's look-ahead needs no bound checks
+
 // Byte offsets of the sections inside the device buffer (each 256-byte aligned).
 struct DeviceLayout {
     int64_t zeros_off = 0, tiles_off = 0, krow_off = 0, perm_off = 0, vals_off = 0, total = 0;
+    int64_t panels_off = 0, pk_meta_off = 0, prow_off = 0;
 };
 
 }  // namespace vbrk
@@ -72,7 +91,20 @@ struct vbr {
     int32_t class_begin[5] = {0, 0, 0, 0, 0};  // tiles of slab class c (1,2,4,8 slabs) are [class_begin[c], class_begin[c+1])
     std::vector<int64_t> group_first_tile;      // [n_groups+1] tiles of a group in creation order (for unpack)
     std::vector<int32_t> tile_of_group_order;   // creation order -> index in `tiles`
-    std::vector<uint16_t> vals;          // packed fragments
+    std::vector<uint16_t> vals;          // packed fragments: tiles first, then panels, then 1 KiB of zeros
+    // panels: rows of groups of height < 16 (when the block width is a multiple of 8)
+    int32_t panel_slabs = 0;             // slabs per panel (16 or 32); 0 = the matrix has no panels
+    std::vector<int32_t> prow;           // original row of every panel-region row, in permuted order
+    std::vector<int32_t> group_prow;     // [n_groups] first panel-region row of a short group, -1 for tall groups
+    std::vector<vbrk::PanelDesc> panels;
+    std::vector<int32_t> pk_row;         // host only: first B row of each granule of each physical K-step, -1 = padding
+    std::vector<uint32_t> pk_mask;       // host only: slabs present in each physical K-step
+    std::vector<int32_t> pk_meta;        // device: per physical K-step one record {mask, granule rows...}; each panel's
+                                         // records are followed by kPanelMetaPad records {0, rows of its last step}
+    std::vector<int32_t> pk_logical;     // host only: K-step number inside the panel's union (a split step repeats it)
+    std::vector<int64_t> pk_frag;        // host only: ordinal of the step's first fragment inside its panel
+    std::vector<int64_t> p_union_ptr;    // host only: [n_panels+1] into p_union
+    std::vector<int32_t> p_union;        // host only: ascending union of the column blocks of each panel
     vbrk::DeviceLayout lay;
     void *dev = nullptr;                 // uploaded buffer (caller-owned)
 };

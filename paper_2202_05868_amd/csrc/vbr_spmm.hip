@@ -229,10 +229,12 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
                 b_off[f] = R0 * kRowBytes + ((chunk ^ (2 * (R0 & 7))) << 4) + (s16 & 1) * 8;
             }
         }
-        auto compute = [&](int bslot, int aslot) {
+        // the LDS reads of a K-step are issued before the next loads (the inline asm keeps that
+        // order), so that their latency overlaps with the address work of the loads
+        short8v bfrag[4], afrag[S];
+        auto read_frags = [&](int bslot, int aslot) {
             const lds_u8_ptr sb = sm + bslot * kPanelBytes;
             const lds_u8_ptr sa = sm + kBRing + aslot * kAStage;
-            short8v bfrag[4];
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sb + b_off[f]));
@@ -240,13 +242,15 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
                 bfrag[f] = short8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             }
 #pragma unroll
-            for (int s = 0; s < S; ++s) {
-                const short8v afrag = *(lds_short8_ptr)(sa + s * kFragBytes + lane * 16);
-                // operands swapped: the result tile comes out transposed, so a lane holds 4
-                // consecutive columns of one C row and stores them as one 16-byte word
+            for (int s = 0; s < S; ++s) afrag[s] = *(lds_short8_ptr)(sa + s * kFragBytes + lane * 16);
+        };
+        auto multiply = [&]() {
+            // operands swapped: the result tile comes out transposed, so a lane holds 4 consecutive
+            // columns of one C row and stores them as one 16-byte word
 #pragma unroll
-                for (int f = 0; f < 4; ++f) acc[s][f] = mfma16x16x32<DT>(bfrag[f], afrag, acc[s][f]);
-            }
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) acc[s][f] = mfma16x16x32<DT>(bfrag[f], afrag[s], acc[s][f]);
         };
 
         // ---- software pipeline over the K-steps.  Issue order, as if the loop had started NS-1
@@ -268,11 +272,13 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
         for (int ks = 0; ks < n_ks; ++ks) {
             wait_vmcnt<kWait>();                   // this wave's loads of K-step ks have landed
             __builtin_amdgcn_s_barrier();          // ... and everybody else's; the slots of K-step ks-1 are free
+            asm volatile("" ::"s"(rb0));           // the scalar row lookup is waited for here, not behind the LDS reads
+            read_frags(bslot, aslot);
             issue_b(ks + NS - 1, bslot == 0 ? NS - 1 : bslot - 1);
+            issue_a(ks + DA, aslot == 0 ? NAS - 1 : aslot - 1);
+            multiply();
             rb0 = rb1;
             rb1 = load_rows(ks + NS + 1);
-            issue_a(ks + DA, aslot == 0 ? NAS - 1 : aslot - 1);
-            compute(bslot, aslot);
             bslot = bslot == NS - 1 ? 0 : bslot + 1;
             aslot = aslot == NAS - 1 ? 0 : aslot + 1;
         }
@@ -298,6 +304,214 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
 // Measured on the 16-row workload: two ring slots and four resident workgroups per CU (36 KiB of
 // LDS each) beat deeper rings with fewer workgroups; the gather is bound by how many independent
 // instruction streams feed the texture-address unit, not by the depth of any one of them.
+struct PanelParams {
+    const PanelDesc *panels;
+    const int32_t *pk_meta;   // K-step stream: records {mask, first B row of each granule}
+    const int32_t *prow;
+    const uint16_t *vals;
+    const uint16_t *zfrag;    // 1 KiB of zeros (behind the last fragment): source of the filler loads
+    const uint16_t *zeros;
+    const uint16_t *B;
+    float *C;
+    int64_t ldb, ldc;
+    int32_t N;
+    int32_t lg_gran;          // >= 3
+    int32_t n_panels;         // T
+    int32_t n_ntiles;         // Q = ceil(N / 128)
+};
+
+// Panel kernel: one workgroup (8 waves) owns R slabs (R * 16 rows of short row groups, whatever
+// group they belong to) and 128 columns of C, and walks the union of the column blocks of those
+// groups.  A B row panel is brought into LDS once per K-step for all R slabs; a slab multiplies only
+// in the K-steps where its own groups store a block (mask bit), and only those fragments exist in
+// memory.  Waves form a 2 x 4 grid: wave (wr, wc) owns slabs [wr R/2, (wr+1) R/2) x columns
+// [32 wc, 32 wc + 32).  A direct-to-LDS load costs the CU about 22 cycles whatever its lane mask, so
+// the unit of cost is the load instruction: per K-step 8 for B (1 KiB each) and 8 for A (one
+// fragment each; the host splits K-steps that carry more than 8 fragments).
+constexpr int kPanelThreads = 512;
+template <int DT, int R, int NS, int DA>
+__global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const PanelParams p)
+{
+    static_assert(NS >= 2 && (NS & (NS - 1)) == 0 && DA == NS - 1, "one ring index for both rings: a power of two, A issued with its B");
+    constexpr int kPN = 128;                       // C columns per workgroup
+    constexpr int kPRow = kPN * 2;                 // one staged B row: 256 bytes
+    constexpr int kPPanel = kStepK * kPRow;        // 8 KiB of B per K-step
+    constexpr int kAStage = kPanelMaxFrags * kFragBytes;
+    constexpr int NAS = NS;
+    constexpr int kBRing = NS * kPPanel;
+    constexpr int HS = R / 2;                      // slabs per wave
+    // per K-step a wave issues one B load, then one A load; both of K-step ks must have landed
+    constexpr int kWait = (NS - 2) * 2;
+    static_assert(kWait < 64, "vmcnt is a 6-bit counter");
+    static_assert(kPanelMaxFrags == 8, "one fragment load per wave per K-step");
+    static_assert(kPanelMetaPad >= NS + 3, "look-ahead of the K-step stream");
+    // 2 KiB of slack: the fragment chain reads up to two fragments past the ones it uses
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kBRing + NAS * kAStage + 2 * kFragBytes];
+
+    const int T = p.n_panels, Q = p.n_ntiles;
+    const int x = blockIdx.x & (kXcd - 1), j = blockIdx.x >> 3;
+    int tile, ntile;
+    if (Q >= kXcd) {
+        ntile = x + kXcd * (j / T);
+        tile = j % T;
+        if (ntile >= Q) return;
+    } else {
+        ntile = x % Q;
+        const int member = x / Q, members = (kXcd - ntile + Q - 1) / Q;
+        tile = member + members * j;
+        if (tile >= T) return;
+    }
+    const PanelDesc pd = p.panels[tile];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 2, wc = wave & 3;
+    const int n0 = ntile * kPN;
+    const lds_u8_ptr sm = (lds_u8_ptr)(&smem[0]);
+    const uint32_t smem_base = (uint32_t)(uintptr_t)sm;
+    const char *zeros = reinterpret_cast<const char *>(p.zeros);
+    const int n_ks = pd.n_ks;
+    const int q = lane >> 4, s16 = lane & 15;
+
+    float4v acc[HS][2];
+#pragma unroll
+    for (int s = 0; s < HS; ++s)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) acc[s][f] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    if (n_ks > 0) {
+        // ---- B staging: per K-step every wave issues 1 load: rows 4 wave + (lane / 16) of the
+        // K-step, 256 bytes each (16 lanes), into 1 KiB of LDS.  LDS chunk c' of row r holds
+        // global chunk c' ^ 2 (r % 8), which spreads the rows of a transposed read over all banks.
+        const int lg = p.lg_gran;
+        const int gmask = (1 << lg) - 1;
+        const int rec = 1 + (kStepK >> lg);                       // int32 per K-step record
+        const const_i32_ptr meta = (const_i32_ptr)p.pk_meta + (int64_t)pd.meta_begin * rec;
+        // three readers walk the stream: the row lookup of the B loads, the mask of the A loads,
+        // the mask of the multiply; each is a pointer that advances by one record per K-step
+        const_i32_ptr p_rb = meta + 1 + ((4 * wave) >> lg), p_ma = meta, p_mc = meta;
+        const uint32_t ldb_bytes = (uint32_t)(p.ldb * 2);
+        const char *Btile = reinterpret_cast<const char *>(p.B) + (int64_t)n0 * 2;
+        const bool tile_fast = n0 + kPN <= p.N;
+        const int rk = 4 * wave + q;                                // this lane's row of the K-step
+        const int b_chunk = s16 ^ (2 * (rk & 7));
+        const uint32_t b_col = b_chunk * 16;
+        const bool b_col_ok = n0 + b_chunk * 8 < p.N;
+        const uint32_t b_lane = (uint32_t)(rk & gmask) * ldb_bytes + b_col;
+        auto next_rows = [&]() -> int { const int v = *p_rb; p_rb += rec; return v; };
+        auto next_ma = [&]() -> uint32_t { const uint32_t v = (uint32_t)*p_ma; p_ma += rec; return v; };
+        auto next_mc = [&]() -> uint32_t { const uint32_t v = (uint32_t)*p_mc; p_mc += rec; return v; };
+        int rb0, rb1;
+        auto issue_b = [&](int slot) {
+            const uint32_t sb = smem_base + slot * kPPanel + 4 * wave * kPRow;
+            if (tile_fast && rb0 >= 0) {
+                dma16_base(b_lane, Btile + (uint32_t)rb0 * ldb_bytes, sb);
+            } else {
+                const char *src = (rb0 >= 0 && b_col_ok) ? Btile + (int64_t)(rb0 + (rk & gmask)) * ldb_bytes + b_col : zeros;
+                dma16(src, sb);
+            }
+        };
+        // ---- A staging: the fragments of a K-step follow each other in memory, one per present
+        // slab in rising slab order; fragment i is loaded by wave i.  Every wave issues one load
+        // per K-step whatever the count: a wave without a fragment loads 1 KiB of zeros instead.
+        const char *a_next = reinterpret_cast<const char *>(p.vals) + pd.a_off * 16;
+        const char *zfrag = reinterpret_cast<const char *>(p.zfrag);
+        uint32_t mA0, mA1;
+        auto issue_a = [&](int slot) {
+            const uint32_t sa = smem_base + kBRing + slot * kAStage;
+            const int cnt = __builtin_popcount(mA0);
+            dma16_base(lane * 16, wave < cnt ? a_next + wave * kFragBytes : zfrag, sa + wave * kFragBytes);
+            a_next += cnt * kFragBytes;
+        };
+
+        uint32_t b_off[2];
+        {
+            const int R0 = 16 * (q >> 1) + 4 * (q & 1) + (s16 >> 2);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                const int chunk = 4 * wc + 2 * f + ((s16 & 3) >> 1);
+                b_off[f] = R0 * kPRow + ((chunk ^ (2 * (R0 & 7))) << 4) + (s16 & 1) * 8;
+            }
+        }
+        // the LDS reads of a K-step are issued before the next loads (the inline asm keeps that
+        // order): B fragments of the wave's 32 columns and the first of its A fragments
+        short8v bfrag[2], a_nxt;
+        lds_u8_ptr fa;
+        auto read_frags = [&](int bslot, int aslot, uint32_t m) {
+            const lds_u8_ptr sb = sm + bslot * kPPanel;
+            fa = sm + kBRing + aslot * kAStage + __builtin_popcount(m & ((1u << (wr * HS)) - 1u)) * kFragBytes + lane * 16;
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sb + b_off[f]));
+                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sb + b_off[f] + 8 * kPRow));
+                bfrag[f] = short8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+            a_nxt = *(lds_short8_ptr)fa;
+        };
+        auto multiply = [&](uint32_t mh) {
+            // the fragments of this wave's present slabs follow each other: read one ahead
+#pragma unroll
+            for (int s = 0; s < HS; ++s) {
+                if (mh >> s & 1) {
+                    const short8v a_cur = a_nxt;
+                    fa += kFragBytes;
+                    a_nxt = *(lds_short8_ptr)fa;
+#pragma unroll
+                    for (int f = 0; f < 2; ++f) acc[s][f] = mfma16x16x32<DT>(bfrag[f], a_cur, acc[s][f]);
+                }
+            }
+        };
+
+        // ---- software pipeline: K-steps 0 .. NS-2 are issued up front (B then A each); iteration
+        // ks issues K-step ks+NS-1 into the slot K-step ks-1 has left.  K-steps past the end are
+        // filler records of the stream (mask 0, rows of the last step), so the loads in flight per
+        // wave never change in number.
+        rb0 = next_rows();
+        rb1 = next_rows();
+        mA0 = next_ma();
+        mA1 = next_ma();
+#pragma unroll
+        for (int t = 0; t < NS - 1; ++t) {
+            issue_b(t);
+            issue_a(t);
+            rb0 = rb1; mA0 = mA1;
+            rb1 = next_rows();
+            mA1 = next_ma();
+        }
+        uint32_t mC0 = next_mc(), mC1 = next_mc();
+        for (int ks = 0; ks < n_ks; ++ks) {
+            wait_vmcnt<kWait>();
+            __builtin_amdgcn_s_barrier();
+            // scalar lookups (issued at the end of earlier iterations) are waited for here, not behind the LDS reads
+            asm volatile("" ::"s"(rb0), "s"(mA0), "s"(mC0));
+            const int cur = ks & (NS - 1), fill = (ks - 1) & (NS - 1);
+            const uint32_t mh = (mC0 >> (wr * HS)) & ((1u << HS) - 1u);      // this wave's slabs
+            if (mh != 0) read_frags(cur, cur, mC0);
+            issue_b(fill);
+            issue_a(fill);
+            if (mh != 0) multiply(mh);
+            rb0 = rb1; mA0 = mA1; mC0 = mC1;
+            rb1 = next_rows();
+            mA1 = next_ma();
+            mC1 = next_mc();
+        }
+        wait_vmcnt<0>();
+    }
+
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+        const int rr = (wr * HS + s) * kSlabRows + s16;
+        if (rr < pd.n_rows) {
+            const int64_t orig = p.prow[pd.row_begin + rr];
+            float *crow = p.C + orig * p.ldc;
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                const int n = n0 + wc * 32 + 16 * f + 4 * q;
+                if (n < p.N) *reinterpret_cast<float4v *>(crow + n) = acc[s][f];
+            }
+        }
+    }
+}
+
 constexpr int kStages = 2;      // LDS ring of B panels
 
 constexpr int kADistance = 3;   // K-steps the A fragments are requested ahead
@@ -321,10 +535,27 @@ int launch_class(const vbr *v, const Params &base, int cls, hipStream_t stream)
     return VBR_OK;
 }
 
-template <int DT>
-int launch_all(const vbr *v, const Params &p, hipStream_t stream)
+template <int DT, int R, int NS, int DA>
+int launch_panels(const vbr *v, const PanelParams &pp, hipStream_t stream)
 {
-    int rc = launch_class<DT, 1>(v, p, 0, stream);
+    const int64_t T = pp.n_panels, Q = pp.n_ntiles;
+    int64_t grid;
+    if (Q >= kXcd) grid = (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
+    else grid = (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
+    if (grid > INT32_MAX) return VBR_EINVAL;
+    hipLaunchKernelGGL((vbr_spmm_panel_kernel<DT, R, NS, DA>), dim3((unsigned)grid), dim3(kPanelThreads), 0, stream, pp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
+    return VBR_OK;
+}
+
+template <int DT>
+int launch_all(const vbr *v, const Params &p, const PanelParams &pp, hipStream_t stream)
+{
+    int rc = VBR_OK;
+    if (pp.n_panels > 0)     // the panels first: they are the long-running workgroups
+        rc = launch_panels<DT, 16, 4, 3>(v, pp, stream);
+    if (rc == VBR_OK) rc = launch_class<DT, 1>(v, p, 0, stream);
     if (rc == VBR_OK) rc = launch_class<DT, 2>(v, p, 1, stream);
     if (rc == VBR_OK) rc = launch_class<DT, 4>(v, p, 2, stream);
     if (rc == VBR_OK) rc = launch_class<DT, 8>(v, p, 3, stream);
@@ -344,7 +575,10 @@ extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
     const vbrk::DeviceLayout &L = v->lay;
     struct Part { int64_t off; const void *src; size_t bytes; };
     static const unsigned char kZeros[256] = {0};
-    const Part parts[5] = {
+    const Part parts[8] = {
+        {L.panels_off, v->panels.data(), v->panels.size() * sizeof(vbrk::PanelDesc)},
+        {L.pk_meta_off, v->pk_meta.data(), v->pk_meta.size() * 4},
+        {L.prow_off, v->prow.data(), v->prow.size() * 4},
         {L.zeros_off, kZeros, sizeof(kZeros)},
         {L.tiles_off, v->tiles.data(), v->tiles.size() * sizeof(vbrk::TileDesc)},
         {L.krow_off, v->krow.data(), v->krow.size() * 4},
@@ -387,6 +621,21 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     p.lg_gran = v->lg_gran;
     p.n_tiles = 0;
     p.n_ntiles = (int32_t)((N + vbrk::kTileN - 1) / vbrk::kTileN);
+    vbrk::PanelParams pp;
+    pp.panels = reinterpret_cast<const vbrk::PanelDesc *>(d + v->lay.panels_off);
+    pp.pk_meta = reinterpret_cast<const int32_t *>(d + v->lay.pk_meta_off);
+    pp.zfrag = p.vals + (v->vals.size() - vbrk::kFragElems);
+    pp.prow = reinterpret_cast<const int32_t *>(d + v->lay.prow_off);
+    pp.vals = p.vals;
+    pp.zeros = p.zeros;
+    pp.B = p.B;
+    pp.C = C_dev;
+    pp.ldb = ldb;
+    pp.ldc = ldc;
+    pp.N = (int32_t)N;
+    pp.lg_gran = v->lg_gran;
+    pp.n_panels = (int32_t)v->panels.size();
+    pp.n_ntiles = (int32_t)((N + 127) / 128);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    return v->dtype == VBR_F16 ? vbrk::launch_all<VBR_F16>(v, p, stream) : vbrk::launch_all<VBR_BF16>(v, p, stream);
+    return v->dtype == VBR_F16 ? vbrk::launch_all<VBR_F16>(v, p, pp, stream) : vbrk::launch_all<VBR_BF16>(v, p, pp, stream);
 }

@@ -86,6 +86,32 @@ def test_result_does_not_depend_on_the_row_partition_used():
         check_c(c, c_ref, s, name)
 
 
+def test_short_groups_in_panels_with_split_steps():
+    # more than 4096 rows in groups shorter than a slab: the panel kernel; few column blocks at
+    # high density force K-steps with more present slabs than one step carries (split steps)
+    rng = np.random.default_rng(12)
+    csr = random_csr(rng, 6000, 12 * 8, 0.08)
+    b = synth.dense_rhs(rng, 96, 136, "f16")            # one full 128-column tile + a ragged one
+    perm, rg = blocking_bit_exact(csr, 8, 0.9)
+    h = np.diff(rg)
+    assert h[h < 16].sum() >= 4096                       # enough short rows for panels to be used
+    c, v = gpu_spmm(csr, perm, rg, 8, b)
+    index_bit_exact(v, csr, perm, rg, 8)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "panels")
+    # tall and short groups in one matrix: tiles and panels side by side
+    csr = random_csr(rng, 5000, 256, 0.02, dtype="bf16")
+    b = synth.dense_rhs(rng, 256, 264, "bf16")
+    perm = rng.permutation(5000).astype(np.int32)
+    # heights 3, 16, 181, 16, 1, 283, then 4500 rows in groups of 9 (short: they form the panels)
+    rg = np.concatenate([[0, 3, 19, 200, 216, 217, 500], np.arange(509, 5001, 9)]).astype(np.int32)
+    assert rg[-1] == 5000
+    c, v = gpu_spmm(csr, perm, rg, 32, b)
+    index_bit_exact(v, csr, perm, rg, 32)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "tiles and panels mixed")
+
+
 def test_leading_dimensions_and_overwrite():
     rng = np.random.default_rng(6)
     csr = random_csr(rng, 90, 128, 0.1, dtype="bf16")

@@ -118,6 +118,24 @@ def test_build_accepts_any_valid_partition_and_tall_groups():
     assert_same_index(csr, np.arange(300, dtype=np.int32), np.array([0, 300], dtype=np.int32), 4)
 
 
+def test_panels_with_split_steps_unpack_exactly():
+    # more than 4096 rows in groups shorter than a slab: they are packed as panels; 12 column
+    # blocks at high density make most K-steps carry more present slabs than one step takes, so
+    # steps are split; every stored block must still unpack bit-exactly
+    rng = np.random.default_rng(77)
+    csr = random_csr(rng, 6000, 12 * 8, 0.08)
+    perm, rg = assert_same_blocking(csr, 8, 0.9)
+    h = np.diff(rg)
+    assert h[h < 16].sum() >= 4096
+    v = assert_same_index(csr, perm, rg, 8, check_values=False)
+    ix = v.index()
+    grp_of_blk = np.repeat(np.arange(ix["n_groups"]), np.diff(ix["blk_ptr"]))
+    for b in rng.choice(ix["n_blocks"], size=400, replace=False):
+        g = int(grp_of_blk[b])
+        assert np.array_equal(v.unpack_block(int(b), int(rg[g + 1] - rg[g]), 8),
+                              oracle.block_bits(csr, perm, rg, g, int(ix["blk_col"][b]), 8))
+
+
 def test_empty_rows_and_empty_matrix():
     csr = csr_from_rows([[], [1], [], [1, 5]], n_cols=8)
     perm, rg = assert_same_blocking(csr, 2, 0.5)
