@@ -159,11 +159,13 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
             b_lane[i] = (uint32_t)((8 * wave + 2 * i + half) & gmask) * ldb_bytes + b_col[i];
         }
 
-        // ---- A staging: every wave issues NA loads per K-step, each a lane range of one fragment.
+        // ---- A staging.  A direct-to-LDS load costs the CU the same whatever its lane mask, so a
+        // fragment is always one load: with 1 or 2 slabs the waves take turns (K-step a: wave a % 4,
+        // resp. waves 2 (a % 2) + slab), with 4 or 8 slabs every wave loads S/4 fragments per K-step.
         // Lanes of rows a partial last slab does not store are masked off (their LDS bytes keep
         // whatever they held: those fragment rows only feed C rows that are never stored); a wave
         // whose slab does not exist in this tile reloads the tile's last slab instead, so that the
-        // number of loads per wave stays fixed and no load has an empty lane mask.
+        // loads per wave follow a fixed pattern and no load has an empty lane mask.
         const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
         const uint32_t a_stride_bytes = (uint32_t)(((td.n_slabs - 1) * kFragElems + rows_last * kStepK) * 2);
         const char *Abase = reinterpret_cast<const char *>(p.vals) + td.a_off * 16;
@@ -172,15 +174,20 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
         bool a_on[NA];
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            bool part;           // lanes of the fragment this wave loads
-            if constexpr (S == 1) { a_slab[i] = 0; part = q == wave; }
-            else if constexpr (S == 2) { a_slab[i] = wave & 1; part = (lane >> 5) == (wave >> 1); }
-            else { a_slab[i] = wave + 4 * i; part = true; }
+            if constexpr (S == 1) a_slab[i] = 0;
+            else if constexpr (S == 2) a_slab[i] = wave & 1;
+            else a_slab[i] = wave + 4 * i;
             if (a_slab[i] > td.n_slabs - 1) a_slab[i] = td.n_slabs - 1;
             const int rows = (a_slab[i] == td.n_slabs - 1) ? rows_last : kSlabRows;
-            a_on[i] = part && s16 < rows;
+            a_on[i] = s16 < rows;
             a_lane[i] = (uint32_t)((a_slab[i] * kFragElems + (q * rows + s16) * 8) * 2);
         }
+        // does this wave load (part of) the A fragments of K-step a?
+        auto a_turn = [&](int a) -> bool {
+            if constexpr (S == 1) return (a & 3) == wave;
+            else if constexpr (S == 2) return (a & 1) == (wave >> 1);
+            else return true;
+        };
 
         // First B row of the granule holding this wave's 8 rows (blocks at least 8 wide), for the
         // K-step whose B loads are issued next (rb0) and the one after (rb1): scalar loads, issued
@@ -209,12 +216,28 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
             }
         };
         auto issue_a = [&](int ks, int slot) {
+            if (!a_turn(ks)) return;
             const int kc = ks < n_ks ? ks : n_ks - 1;
             const char *kptr = Abase + (int64_t)kc * a_stride_bytes;             // scalar
             const uint32_t sa = smem_base + kBRing + slot * kAStage;
 #pragma unroll
             for (int i = 0; i < NA; ++i)
                 if (a_on[i]) dma16_base(a_lane[i], kptr, sa + a_slab[i] * kFragBytes);
+        };
+        // wait until this wave's loads of K-step ks have landed: everything but the loads it issued
+        // after the B panel of ks, i.e. in the iterations ks-NS+1 (its A part) .. ks-1
+        auto wait_stage = [&](int ks) {
+            if constexpr (S >= 4) {
+                wait_vmcnt<kWait>();
+            } else {
+                int later_a = 0;
+#pragma unroll
+                for (int d = 1; d <= NS - 1; ++d) later_a += a_turn(ks - d + DA) ? 1 : 0;
+                if (later_a == 0) wait_vmcnt<(NS - 2) * 4>();
+                else if (later_a == 1) wait_vmcnt<(NS - 2) * 4 + 1>();
+                else wait_vmcnt<(NS - 2) * 4 + 2>();
+                static_assert(NS <= 3, "at most two later A loads are told apart");
+            }
         };
 
         // B fragment of MFMA tile f, half r: lane (q, s16) reads 8 bytes of B row
@@ -270,7 +293,7 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
         }
         int bslot = 0, aslot = 0;
         for (int ks = 0; ks < n_ks; ++ks) {
-            wait_vmcnt<kWait>();                   // this wave's loads of K-step ks have landed
+            wait_stage(ks);                        // this wave's loads of K-step ks have landed
             __builtin_amdgcn_s_barrier();          // ... and everybody else's; the slots of K-step ks-1 are free
             asm volatile("" ::"s"(rb0));           // the scalar row lookup is waited for here, not behind the LDS reads
             read_frags(bslot, aslot);
