@@ -92,8 +92,27 @@ __device__ __forceinline__ void wait_vmcnt()
 // The loop is bound by the instructions a wave needs per K-step, so the common case (block width a
 // multiple of 8, full column tile, no padding rows in the K-step) is kept to a handful of scalar
 // instructions per 1 KiB load; everything else takes the general path.
+// Workgroup -> (tile, column tile).  Workgroups are dealt to the 8 L2 domains round-robin; a
+// domain keeps to few column tiles so that the B columns it gathers stay in its L2.
+__device__ __forceinline__ bool map_workgroup(int T, int Q, int &tile, int &ntile)
+{
+    const int x = blockIdx.x & (kXcd - 1), j = blockIdx.x >> 3;
+    if (Q >= kXcd) {
+        ntile = x + kXcd * (j / T);
+        tile = j % T;
+        return ntile < Q;
+    }
+    ntile = x % Q;
+    const int member = x / Q, members = (kXcd - ntile + Q - 1) / Q;
+    tile = member + members * j;
+    return tile < T;
+}
+
+template <int S, int NS, int DA>
+constexpr int tile_lds_bytes() { return NS * kPanelBytes + (DA + 1) * S * kFragBytes; }
+
 template <int DT, int S, int NS, int DA>
-__global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
+__device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, const int ntile, unsigned char *smem)
 {
     static_assert(NS >= 2 && DA >= NS - 1, "A must be requested before the B panel of its K-step");
     constexpr int NA = S >= 4 ? S / 4 : 1;      // A loads per wave per K-step
@@ -103,28 +122,11 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
     // loads younger than the last B load of K-step ks when the workgroup waits for it
     constexpr int kWait = (NS - 2) * 4 + (NS - 1) * NA;
     static_assert(kWait < 64, "vmcnt is a 6-bit counter");
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[kBRing + NAS * kAStage];
 
-    // Workgroup -> (tile, column tile).  Workgroups are dealt to the 8 L2 domains round-robin;
-    // a domain keeps to few column tiles so that the B columns it gathers stay in its L2.
-    const int T = p.n_tiles, Q = p.n_ntiles;
-    const int x = blockIdx.x & (kXcd - 1), j = blockIdx.x >> 3;
-    int tile, ntile;
-    if (Q >= kXcd) {
-        ntile = x + kXcd * (j / T);
-        tile = j % T;
-        if (ntile >= Q) return;
-    } else {
-        ntile = x % Q;
-        const int member = x / Q, members = (kXcd - ntile + Q - 1) / Q;
-        tile = member + members * j;
-        if (tile >= T) return;
-    }
-    const TileDesc td = p.tiles[tile];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = ntile * kTileN;
-    const lds_u8_ptr sm = (lds_u8_ptr)(&smem[0]);
+    const lds_u8_ptr sm = (lds_u8_ptr)smem;
     const uint32_t smem_base = (uint32_t)(uintptr_t)sm;      // LDS byte address, for M0
     const char *zeros = reinterpret_cast<const char *>(p.zeros);
     const int n_ks = td.n_ks;
@@ -327,6 +329,30 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
 // Measured on the 16-row workload: two ring slots and four resident workgroups per CU (36 KiB of
 // LDS each) beat deeper rings with fewer workgroups; the gather is bound by how many independent
 // instruction streams feed the texture-address unit, not by the depth of any one of them.
+template <int DT, int S, int NS, int DA>
+__global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[tile_lds_bytes<S, NS, DA>()];
+    int tile, ntile;
+    if (!map_workgroup(p.n_tiles, p.n_ntiles, tile, ntile)) return;
+    tile_body<DT, S, NS, DA>(p, p.tiles[tile], ntile, smem);
+}
+
+// All slab classes in one launch, for matrices whose classes are each too small to fill the chip:
+// the workgroup picks the code of its tile's class (registers and LDS are those of the largest).
+template <int DT, int NS, int DA>
+__global__ void __launch_bounds__(kThreads) vbr_spmm_mixed_kernel(const Params p)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[tile_lds_bytes<8, NS, DA>()];
+    int tile, ntile;
+    if (!map_workgroup(p.n_tiles, p.n_ntiles, tile, ntile)) return;
+    const TileDesc td = p.tiles[tile];
+    if (td.n_slabs <= 1) tile_body<DT, 1, NS, DA>(p, td, ntile, smem);
+    else if (td.n_slabs <= 2) tile_body<DT, 2, NS, DA>(p, td, ntile, smem);
+    else if (td.n_slabs <= 4) tile_body<DT, 4, NS, DA>(p, td, ntile, smem);
+    else tile_body<DT, 8, NS, DA>(p, td, ntile, smem);
+}
+
 struct PanelParams {
     const PanelDesc *panels;
     const int32_t *pk_meta;   // K-step stream: records {mask, first B row of each granule}
@@ -371,19 +397,8 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
     // 2 KiB of slack: the fragment chain reads up to two fragments past the ones it uses
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kBRing + NAS * kAStage + 2 * kFragBytes];
 
-    const int T = p.n_panels, Q = p.n_ntiles;
-    const int x = blockIdx.x & (kXcd - 1), j = blockIdx.x >> 3;
     int tile, ntile;
-    if (Q >= kXcd) {
-        ntile = x + kXcd * (j / T);
-        tile = j % T;
-        if (ntile >= Q) return;
-    } else {
-        ntile = x % Q;
-        const int member = x / Q, members = (kXcd - ntile + Q - 1) / Q;
-        tile = member + members * j;
-        if (tile >= T) return;
-    }
+    if (!map_workgroup(p.n_panels, p.n_ntiles, tile, ntile)) return;
     const PanelDesc pd = p.panels[tile];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -578,6 +593,21 @@ int launch_all(const vbr *v, const Params &p, const PanelParams &pp, hipStream_t
     int rc = VBR_OK;
     if (pp.n_panels > 0)     // the panels first: they are the long-running workgroups
         rc = launch_panels<DT, 16, 4, 3>(v, pp, stream);
+    // several classes, none of which alone gives every CU a couple of workgroups: one mixed launch
+    int classes = 0;
+    for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
+    const int64_t T_all = v->class_begin[4];
+    if (rc == VBR_OK && classes > 1 && T_all * p.n_ntiles < 4096) {
+        Params pm = p;
+        pm.n_tiles = (int32_t)T_all;
+        const int64_t Q = pm.n_ntiles;
+        const int64_t grid = Q >= kXcd ? (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T_all
+                                        : (int64_t)kXcd * ((T_all + (kXcd / Q) - 1) / (kXcd / Q));
+        hipLaunchKernelGGL((vbr_spmm_mixed_kernel<DT, kStages, kADistance>), dim3((unsigned)grid), dim3(kThreads), 0, stream, pm);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
+        return VBR_OK;
+    }
     if (rc == VBR_OK) rc = launch_class<DT, 1>(v, p, 0, stream);
     if (rc == VBR_OK) rc = launch_class<DT, 2>(v, p, 1, stream);
     if (rc == VBR_OK) rc = launch_class<DT, 4>(v, p, 2, stream);
