@@ -11,6 +11,8 @@
 #include <numeric>
 #include <vector>
 
+#include <immintrin.h>
+
 #include "vbr_host.h"
 
 namespace vbrk {
@@ -40,11 +42,34 @@ int validate_csr(const vbr_csr_t *csr, bool need_vals)
 
 namespace {
 
-inline int64_t popcount_and(const uint64_t *a, const uint64_t *b, int64_t w)
+int64_t popcount_and_generic(const uint64_t *a, const uint64_t *b, int64_t w)
 {
     int64_t s = 0;
     for (int64_t i = 0; i < w; ++i) s += __builtin_popcountll(a[i] & b[i]);
     return s;
+}
+
+// Same count with 512-bit AND + per-lane population count, where the host CPU has them
+// (checked once at run time: the library is built on one machine and run on another).
+__attribute__((target("avx512f,avx512vpopcntdq")))
+int64_t popcount_and_avx512(const uint64_t *a, const uint64_t *b, int64_t w)
+{
+    __m512i acc = _mm512_setzero_si512();
+    int64_t i = 0;
+    for (; i + 8 <= w; i += 8)
+        acc = _mm512_add_epi64(acc, _mm512_popcnt_epi64(_mm512_and_si512(_mm512_loadu_si512(a + i), _mm512_loadu_si512(b + i))));
+    int64_t s = _mm512_reduce_add_epi64(acc);
+    for (; i < w; ++i) s += __builtin_popcountll(a[i] & b[i]);
+    return s;
+}
+
+typedef int64_t (*popcount_and_fn)(const uint64_t *, const uint64_t *, int64_t);
+
+popcount_and_fn pick_popcount_and()
+{
+    __builtin_cpu_init();
+    if (__builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512vpopcntdq")) return popcount_and_avx512;
+    return popcount_and_generic;
 }
 
 }  // namespace
@@ -118,48 +143,144 @@ int sa1_reorder_impl(const vbr_csr_t *csr, int32_t col_block, double tau, int32_
     bits.clear();
     bits.shrink_to_fit();
 
-    // Algorithm 2.  `active` holds the classes not yet grouped, in rising order; one pass per
-    // seed scans it once, merging where the condition of section 3.2 holds and OR-ing the
-    // merged pattern into the group's pattern.
+    // Algorithm 2: one pass per seed over the later ungrouped classes in rising order, merging
+    // where the condition of section 3.2 holds and OR-ing the merged pattern into the group's.
+    const popcount_and_fn popcount_and = pick_popcount_and();
+    // The similarity test (double)I / (double)U >= tau is monotone in I for a fixed U, so it is
+    // tabulated once: need[U] = smallest I that passes (found with the very same division, so
+    // the decisions are bit-identical), need[0] = 0 (two empty patterns are similar).
+    std::vector<int32_t> need((size_t)KB + 1, 0);
+    for (int64_t U = 1; U <= KB; ++U) {
+        int64_t I = (int64_t)std::ceil(tau * (double)U);
+        I = std::max<int64_t>(0, std::min<int64_t>(I, U));
+        while (I > 0 && (double)(I - 1) / (double)U >= tau) --I;
+        while (I <= U && !((double)I / (double)U >= tau)) ++I;      // I = U + 1: nothing passes
+        need[U] = (int32_t)I;
+    }
     std::vector<int32_t> group_of(std::max<int64_t>(NC, 1), -1);
-    std::vector<int32_t> active(NC), keep;
-    std::iota(active.begin(), active.end(), 0);
-    keep.reserve(NC);
     std::vector<uint64_t> P(W);
     int32_t G = 0;
-    while (!active.empty()) {
-        const int32_t seed = active[0];
-        group_of[seed] = G;
-        std::memcpy(P.data(), &cbits[(size_t)seed * W], (size_t)W * 8);
-        int64_t sizeP = clen[seed];
-        const int64_t lambda0 = sizeP;
-        const int64_t lam_max = (int64_t)std::floor((double)lambda0 / (1.0 - 0.5 * tau));
-        keep.clear();
-        for (size_t t = 1; t < active.size(); ++t) {
-            const int32_t j = active[t];
-            const int64_t lv = clen[j];
-            bool merge = false;
-            if (sizeP == 0 && lv == 0) {
-                merge = true;                         // both empty: similar, union 0 within any limit
-            } else {
-                // |P & v| <= min and |P | v| >= max: if even min/max misses tau the exact ratio does too
-                const int64_t lo = std::min(sizeP, lv), hi = std::max(sizeP, lv);
-                if ((double)lo / (double)hi >= tau && hi <= lam_max) {
+    // the merge test for class j against the current pattern; updates the pattern on success
+    int64_t sizeP = 0, lam_max = 0;
+    auto try_merge = [&](int32_t j) -> bool {
+        const int64_t lv = clen[j];
+        if (sizeP == 0 && lv == 0) return true;            // both empty: similar, union 0 within any limit
+        // |P & v| <= min and |P | v| >= max: if even min/max misses tau the exact ratio does too
+        const int64_t lo = std::min(sizeP, lv), hi = std::max(sizeP, lv);
+        if (lo < need[hi] || hi > lam_max) return false;
+        const uint64_t *v = &cbits[(size_t)j * W];
+        const int64_t I = popcount_and(P.data(), v, W);
+        const int64_t U = sizeP + lv - I;
+        if (I < need[U] || U > lam_max) return false;
+        for (int64_t w = 0; w < W; ++w) P[w] |= v[w];
+        sizeP = U;
+        return true;
+    };
+
+    if (need[std::min<int64_t>(1, KB)] == 0) {
+        // tau == 0: a class that shares nothing with the pattern can still pass the similarity
+        // test, so every later class has to be looked at.  `active` = ungrouped classes, rising.
+        std::vector<int32_t> active(NC), keep;
+        std::iota(active.begin(), active.end(), 0);
+        keep.reserve(NC);
+        while (!active.empty()) {
+            const int32_t seed = active[0];
+            group_of[seed] = G;
+            std::memcpy(P.data(), &cbits[(size_t)seed * W], (size_t)W * 8);
+            sizeP = clen[seed];
+            lam_max = (int64_t)std::floor((double)sizeP / (1.0 - 0.5 * tau));
+            keep.clear();
+            for (size_t t = 1; t < active.size(); ++t) {
+                if (try_merge(active[t])) group_of[active[t]] = G;
+                else keep.push_back(active[t]);
+            }
+            active.swap(keep);
+            ++G;
+        }
+    } else {
+        // tau > 0: a class can only pass if it shares a column block with the pattern (I >= 1).
+        // An inverted index (block -> rising list of classes holding it) gives exactly those
+        // classes: walking the lists of the pattern's blocks and counting how often a class shows
+        // up yields |P & v| itself, with no bitset work.  Touched classes are flagged in a bitmap
+        // and visited in rising order; when a merge adds blocks to the pattern, the tails of their
+        // lists (classes above the current one) are counted in as well.  Every class that could
+        // pass is met in the same order and with the same counts as in the full scan.
+        std::vector<int64_t> inv_ptr((size_t)KB + 1, 0);
+        for (int64_t c = 0; c < NC; ++c)
+            for (int64_t w = 0; w < W; ++w)
+                for (uint64_t x = cbits[(size_t)c * W + w]; x; x &= x - 1) inv_ptr[(w << 6) + __builtin_ctzll(x) + 1]++;
+        for (int64_t b = 0; b < KB; ++b) inv_ptr[b + 1] += inv_ptr[b];
+        std::vector<int32_t> inv((size_t)inv_ptr[KB]);
+        {
+            std::vector<int64_t> fill(inv_ptr.begin(), inv_ptr.end() - 1);
+            for (int64_t c = 0; c < NC; ++c)
+                for (int64_t w = 0; w < W; ++w)
+                    for (uint64_t x = cbits[(size_t)c * W + w]; x; x &= x - 1) inv[fill[(w << 6) + __builtin_ctzll(x)]++] = (int32_t)c;
+        }
+        std::vector<int64_t> first(inv_ptr.begin(), inv_ptr.end() - 1);   // per block: first list entry above the seeds done
+        std::vector<int32_t> cnt((size_t)std::max<int64_t>(NC, 1), 0);    // |P & v| of the touched classes
+        const int64_t BW = (NC + 63) / 64 + 1;
+        std::vector<uint64_t> touched((size_t)BW, 0);
+        std::vector<uint64_t> before(W);
+        auto count_list = [&](int64_t b, int32_t above) {                  // classes of block b above `above`
+            int64_t &f = first[b];
+            while (f < inv_ptr[b + 1] && inv[f] <= above) ++f;             // classes only rise: skipped for good
+            for (int64_t e = f; e < inv_ptr[b + 1]; ++e) {
+                const int32_t c = inv[e];
+                ++cnt[c];
+                touched[c >> 6] |= 1ull << (c & 63);
+            }
+        };
+        for (int32_t seed = 0; seed < NC; ++seed) {
+            if (group_of[seed] != -1) continue;
+            group_of[seed] = G;
+            std::memcpy(P.data(), &cbits[(size_t)seed * W], (size_t)W * 8);
+            sizeP = clen[seed];
+            lam_max = (int64_t)std::floor((double)sizeP / (1.0 - 0.5 * tau));
+            // dense patterns make the lists long: when walking them costs more than comparing
+            // bitsets with every later class, do that instead (same decisions either way)
+            int64_t list_work = 0;
+            for (int64_t w = 0; w < W; ++w)
+                for (uint64_t x = P[w]; x; x &= x - 1) {
+                    const int64_t b = (w << 6) + __builtin_ctzll(x);
+                    list_work += inv_ptr[b + 1] - first[b];
+                }
+            if (list_work > 4 * W * (NC - seed)) {
+                for (int32_t j = seed + 1; j < NC; ++j)
+                    if (group_of[j] == -1 && try_merge(j)) group_of[j] = G;
+                ++G;
+                continue;
+            }
+            for (int64_t w = 0; w < W; ++w)
+                for (uint64_t x = P[w]; x; x &= x - 1) count_list((w << 6) + __builtin_ctzll(x), seed);
+            for (int64_t tw = seed >> 6; tw < BW; ++tw) {
+                while (touched[tw]) {
+                    const int32_t j = (int32_t)((tw << 6) + __builtin_ctzll(touched[tw]));
+                    touched[tw] &= touched[tw] - 1;
+                    const int64_t I = cnt[j];
+                    cnt[j] = 0;
+                    if (group_of[j] != -1) continue;
+                    const int64_t U = sizeP + clen[j] - I;
+                    if (I < need[U] || U > lam_max) continue;
+                    group_of[j] = G;                                        // merge: pattern <- OR
                     const uint64_t *v = &cbits[(size_t)j * W];
-                    const int64_t I = popcount_and(P.data(), v, W);
-                    const int64_t U = sizeP + lv - I;
-                    if ((double)I / (double)U >= tau && U <= lam_max) {
-                        merge = true;
-                        for (int64_t w = 0; w < W; ++w) P[w] |= v[w];
-                        sizeP = U;
-                    }
+                    for (int64_t w = 0; w < W; ++w) { before[w] = P[w]; P[w] |= v[w]; }
+                    sizeP = U;
+                    for (int64_t w = 0; w < W; ++w)                         // tails of the lists of the new blocks
+                        for (uint64_t x = P[w] & ~before[w]; x; x &= x - 1) {
+                            const int64_t b = (w << 6) + __builtin_ctzll(x);
+                            const int64_t lo = std::max(first[b], inv_ptr[b]);
+                            for (int64_t e = std::upper_bound(inv.begin() + lo, inv.begin() + inv_ptr[b + 1], j) - inv.begin();
+                                 e < inv_ptr[b + 1]; ++e) {
+                                const int32_t c = inv[e];
+                                ++cnt[c];
+                                touched[c >> 6] |= 1ull << (c & 63);
+                            }
+                        }
                 }
             }
-            if (merge) group_of[j] = G;
-            else keep.push_back(j);
+            ++G;
         }
-        active.swap(keep);
-        ++G;
     }
 
     // Rows sorted by group, stable in the row index; groups are already numbered in seed order.

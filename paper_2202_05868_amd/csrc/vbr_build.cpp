@@ -140,6 +140,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     v->p_union_ptr.assign(1, 0);
     std::vector<uint32_t> blk_mask;            // per union block: slabs that store it
     std::vector<int64_t> frag_of;              // [logical step][slab] -> fragment ordinal in the panel, -1
+    std::vector<int64_t> fill_dst, fill_src;   // panel values: position in vals <- position in csr->vals
     const int64_t tiles_units = a_units;       // panels' values follow the tiles'
     for (int64_t pn = 0; pn < n_panels; ++pn) {
         const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
@@ -202,17 +203,18 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             v->pk_meta.push_back(ph < pd.ks_begin + pd.n_ks ? (int32_t)v->pk_mask[ph] : 0);
             for (int e = 0; e < per_step; ++e) v->pk_meta.push_back(v->pk_row[(size_t)src_ph * per_step + e]);
         }
-        // values: one full 16 x 32 fragment per (physical step, present slab)
-        v->vals.resize((size_t)(a_units + n_frags * (kFragElems / 8)) * 8, 0);
-        const uint16_t *src = static_cast<const uint16_t *>(csr->vals);
-        uint16_t *dst = &v->vals[(size_t)a_units * 8];
+        // values: one full 16 x 32 fragment per (physical step, present slab).  Only the target
+        // position of every entry is noted here; the value array is allocated once, at its final
+        // size, after the last panel.
         for (int64_t i = i0; i < i1; ++i) {
             const int64_t r = v->prow[i];
             const int s = (int)((i - i0) / kSlabRows), mrow = (int)((i - i0) % kSlabRows);
             for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
                 const int64_t c = csr->col_idx[p];
                 const int64_t k = (int64_t)pos_of_block[c / col_block] * col_block + c % col_block;
-                dst[frag_of[(size_t)((k / kStepK) * R + s)] * kFragElems + frag_index(mrow, (int)(k % kStepK), kSlabRows)] = src[p];
+                fill_dst.push_back(a_units * 8 + frag_of[(size_t)((k / kStepK) * R + s)] * kFragElems +
+                                   frag_index(mrow, (int)(k % kStepK), kSlabRows));
+                fill_src.push_back(p);
             }
         }
         a_units += n_frags * (kFragElems / 8);
@@ -220,10 +222,13 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         v->panels.push_back(pd);
     }
 
-    // pass 3: values of the tiles into fragments (the tiles' region precedes the panels')
-    if (v->vals.size() < (size_t)a_units * 8) v->vals.resize((size_t)a_units * 8, 0);
+    // pass 3: the values.  One allocation: tiles' fragments, panels' fragments, and one fragment
+    // of zeros behind the last value (loads that run past a panel's data stay inside, and the
+    // panel kernel's filler loads read it).
     (void)tiles_units;
+    v->vals.assign((size_t)a_units * 8 + kFragElems, 0);
     const uint16_t *src = static_cast<const uint16_t *>(csr->vals);
+    for (size_t e = 0; e < fill_dst.size(); ++e) v->vals[(size_t)fill_dst[e]] = src[fill_src[e]];
     for (int32_t g = 0; g < G; ++g) {
         if (v->group_first_tile[g] == v->group_first_tile[g + 1]) continue;
         for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) pos_of_block[v->blk_col[b]] = (int32_t)(b - v->blk_ptr[g]);
@@ -245,8 +250,6 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         }
         for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) pos_of_block[v->blk_col[b]] = -1;
     }
-    // one fragment of zeros behind the last value: loads that run past a panel's data stay inside
-    v->vals.resize(v->vals.size() + kFragElems, 0);
 
     // schedule: tiles grouped by slab class (one kernel instantiation each), heaviest first
     const int64_t NT = (int64_t)tiles.size();

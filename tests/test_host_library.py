@@ -91,6 +91,24 @@ def test_more_than_64_column_blocks_and_hash_collisions():
     assert_same_index(csr, perm, rg, 2)
 
 
+@pytest.mark.parametrize("n_rows,n_blocks,density", [(3000, 600, 0.004), (3000, 600, 0.02), (2500, 40, 0.5),
+                                                     (2000, 130, 0.08)])
+def test_reorder_at_sizes_where_both_scan_strategies_run(n_rows, n_blocks, density):
+    # sparse quotient rows over many column blocks: candidates come from the column blocks' row
+    # lists; dense ones over few blocks: every remaining row is compared.  Rows are drawn from a
+    # few hundred base patterns with noise so that merges, refusals and the size cap all occur.
+    rng = np.random.default_rng(n_rows + n_blocks)
+    base = rng.random((300, n_blocks)) < density
+    rows = []
+    for i in range(n_rows):
+        pat = base[rng.integers(0, 300)] ^ (rng.random(n_blocks) < density * 0.15)
+        rows.append((np.nonzero(pat)[0] * 2 + rng.integers(0, 2)).tolist())
+    csr = csr_from_rows(rows, n_cols=2 * n_blocks, rng=rng)
+    for tau in (0.0, 0.05, 0.3, 0.6, 0.9, 1.0):
+        perm, rg = assert_same_blocking(csr, 2, tau)
+        check_partition_shape(perm, rg, n_rows)
+
+
 @pytest.mark.parametrize("name,scale,noise", [("c1", 1.0, True), ("c1", 1.0, False), ("c2", 0.25, True),
                                                ("c3", 0.125, True), ("c4", 0.125, True), ("c5", 0.0625, True)])
 def test_workloads_small_scale_bit_exact(name, scale, noise):
