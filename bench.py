@@ -31,6 +31,8 @@ WORKLOAD_TEXT = {
     "c3": "configs[2]: A 16384x16384 bf16, heights {16,32,64,128} x 32 blocks at 2%, fill 0.7, N=512, tau=0.6",
     "c4": "configs[3]: pruned-weight-like A 4096x16384 fp16, 16x16 blocks kept at 10%, N=4096, tau=0.5",
     "c5": "configs[4]: Erdos-Renyi A 32768x32768 fp16 density 0.05%, column block 32, N=256, tau=0.3",
+    "rmat": "graph workload of the paper's section 6.2: RMAT (0.57,0.19,0.19,0.05), 2^14 nodes, 32 edges per node, "
+            "rows scrambled, column block 64, N=4096, tau=0.4",
 }
 
 
@@ -42,6 +44,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--clean", action="store_true", help="noise-free variant of c1/c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-csr-baseline", action="store_true",
+                    help="skip the CSR comparator kernel (the stand-in for the sparse-library routine)")
     ap.add_argument("--no-dense-baseline", action="store_true",
                     help="skip the dense product on the zero-filled matrix (run by default for c2 and c4)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -183,6 +187,31 @@ def main() -> int:
         "setup": {"sa1_reorder_s": t1 - t0, "vbr_build_s": t2 - t1, "upload_s": t3 - t2},
         "roofline": roofline,
     }
+
+    if not args.no_csr_baseline:
+        # the comparison of the paper's section 6.2: the same product straight from CSR (own kernel,
+        # fp32 FMAs on the vector units), timed the same way
+        hcsr = binding.CsrDev(a).upload(dev)
+        cc = torch.empty_like(c)
+        for _ in range(2):
+            hcsr.spmm(b, cc)
+        torch.cuda.synchronize()
+        s0 = torch.cuda.Event(enable_timing=True)
+        s1 = torch.cuda.Event(enable_timing=True)
+        s0.record(stream)
+        for _ in range(5):
+            hcsr.spmm(b, cc)
+        s1.record(stream)
+        torch.cuda.synchronize()
+        cms = s0.elapsed_time(s1) / 5
+        out["csr_spmm_baseline"] = {
+            "kind": "own CSR x dense kernel on the same GPU, one wave per row and 512 columns, fp32 accumulation",
+            "ms": cms, "nnz_tflops": flops_nnz / (cms * 1e-3) * 1e-12,
+            "gathered_B_GBs": a["nnz"] * n * 2 / (cms * 1e-3) * 1e-9,
+            "speedup_of_vbr_over_csr": cms / ms,
+            "max_abs_diff_vs_vbr": float((cc - c).abs().max()),
+        }
+        del hcsr, cc
 
     if args.workload in ("c2", "c4") and not args.no_dense_baseline:
         # the dense product on the zero-filled matrix (the comparison the target config names): the

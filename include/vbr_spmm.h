@@ -128,6 +128,41 @@ int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_
 
 void vbr_free(vbr_t *v);
 
+/*
+ * Blocking curve (sections 4.1 and 6.1): run 1-SA once per threshold taus[0 .. n_taus-1] and
+ * report, per threshold, what the VBR matrix of that blocking would hold, without building it:
+ *   n_groups[i]       row groups
+ *   n_blocks[i]       stored (nonzero) blocks
+ *   stored_elems[i]   nonzero area: sum over stored blocks of height * col_block
+ *   sum_heights[i]    sum over stored blocks of their height
+ * so that the in-block density after blocking is rho' = nnz / stored_elems[i] and the average
+ * height of the nonzero blocks is Delta'_H = sum_heights[i] / n_blocks[i] (section 6.1).
+ * *selected is the index of the blocking whose Delta'_H is nearest to target_height (the rule of
+ * section 6.2: take the blocking with Delta'_H ~ Delta), compared exactly in integers; of equally
+ * near ones the first in the order given; a blocking without blocks is never selected unless
+ * none has any (then 0).  Any out array may be NULL.  target_height > 0.
+ */
+int sa1_blocking_curve(const vbr_csr_t *csr, int32_t col_block, const double *taus, int32_t n_taus,
+                       int64_t target_height, int64_t *n_groups, int64_t *n_blocks,
+                       int64_t *stored_elems, int64_t *sum_heights, int32_t *selected);
+
+/*
+ * Comparator: C = A.B straight from the CSR matrix on the GPU, one fp32 accumulator per output
+ * element, no blocking and no matrix units.  It stands where the sparse-library routine stands
+ * in the comparison of section 6.2 and is not part of the blocked path.
+ *   csr_spmm_create   validates the host CSR (canonical form as above) and keeps a copy
+ *   csr_device_bytes  device bytes csr_upload needs (multiple of 256, never 0)
+ *   csr_upload        copies it into buf_dev (caller-allocated, 256-byte aligned) on hip_stream and waits
+ *   csr_spmm          asynchronous on hip_stream; same B / C / N / ldb / ldc rules as vbr_spmm
+ */
+typedef struct csr_dev csr_dev_t;
+int csr_spmm_create(const vbr_csr_t *csr, csr_dev_t **out);
+int64_t csr_device_bytes(const csr_dev_t *h);
+int csr_upload(csr_dev_t *h, void *buf_dev, void *hip_stream);
+int csr_spmm(const csr_dev_t *h, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,
+             int64_t N, void *hip_stream);
+void csr_free(csr_dev_t *h);
+
 const char *vbr_strerror(int code);
 int vbr_last_hip_error(void);   /* hipError_t of the last failing HIP call on this thread */
 

@@ -134,3 +134,29 @@ def spmm(csr: dict, b_bits: np.ndarray, rows=None, with_bound: bool = True):
     if rc != 0:
         raise ValueError("oracle_spmm failed: %d" % rc)
     return c, s
+
+
+def blocking_curve(csr: dict, col_block: int, taus, target_height: int) -> dict:
+    """Blocking curve of section 6.1: for every threshold the blocking of ``sa1`` and, from its
+    VBR index, the number of nonzero blocks, the nonzero area, the in-block density
+    rho' = nnz / area and the average height Delta'_H of the nonzero blocks; ``selected`` is the
+    threshold whose Delta'_H is nearest to ``target_height`` (section 6.2 takes the blocking with
+    Delta'_H ~ Delta; ties go to the first threshold given, empty blockings are skipped)."""
+    from fractions import Fraction
+    rows = []
+    best, best_d = 0, None
+    for i, tau in enumerate(taus):
+        perm, rg = sa1(csr, col_block, float(tau))
+        blk_ptr, blk_col, blk_off = vbr_index(csr, perm, rg, col_block)
+        heights = np.repeat(np.diff(rg).astype(np.int64), np.diff(blk_ptr))     # height of every stored block
+        nb = int(blk_col.size)
+        area = int(blk_off[-1])
+        rows.append(dict(tau=float(tau), n_groups=int(rg.size - 1), n_blocks=nb, stored_elems=area,
+                         sum_heights=int(heights.sum()),
+                         rho=(csr["nnz"] / area) if area else 0.0,
+                         avg_height=(float(heights.mean()) if nb else 0.0)))
+        if nb:
+            d = abs(Fraction(int(heights.sum()), nb) - target_height)
+            if best_d is None or d < best_d:
+                best, best_d = i, d
+    return dict(points=rows, selected=best)

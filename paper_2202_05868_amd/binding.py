@@ -19,7 +19,8 @@ _DTYPES = {"f16": VBR_F16, "bf16": VBR_BF16}
 
 EXPORTS = ("sa1_reorder", "vbr_build", "vbr_get_index", "vbr_unpack_block", "vbr_device_bytes",
            "vbr_upload", "vbr_spmm", "vbr_get_schedule", "vbr_free", "vbr_strerror",
-           "vbr_last_hip_error")
+           "vbr_last_hip_error", "sa1_blocking_curve", "csr_spmm_create", "csr_device_bytes", "csr_upload",
+           "csr_spmm", "csr_free")
 
 
 class VbrError(RuntimeError):
@@ -62,8 +63,16 @@ def _load():
     lib.vbr_strerror.argtypes = [ctypes.c_int]
     lib.vbr_strerror.restype = ctypes.c_char_p
     lib.vbr_last_hip_error.restype = ctypes.c_int
+    lib.sa1_blocking_curve.argtypes = [P(_Csr), i32, vp, i32, i64, vp, vp, vp, vp, P(i32)]
+    lib.csr_spmm_create.argtypes = [P(_Csr), P(vp)]
+    lib.csr_device_bytes.argtypes = [vp]
+    lib.csr_device_bytes.restype = i64
+    lib.csr_upload.argtypes = [vp, vp, vp]
+    lib.csr_spmm.argtypes = [vp, vp, i64, vp, i64, i64, vp]
+    lib.csr_free.argtypes = [vp]
+    lib.csr_free.restype = None
     for name in ("sa1_reorder", "vbr_build", "vbr_get_index", "vbr_unpack_block", "vbr_upload",
-                 "vbr_spmm", "vbr_get_schedule"):
+                 "vbr_spmm", "vbr_get_schedule", "sa1_blocking_curve", "csr_spmm_create", "csr_upload", "csr_spmm"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -214,3 +223,77 @@ def vbr_build(csr: dict, perm: np.ndarray, row_groups: np.ndarray, col_block: in
 
 def vbr_spmm(v: Vbr, b, c=None, n_rows: int | None = None):
     return v.spmm(b, c, n_rows)
+
+
+def sa1_blocking_curve(csr: dict, col_block: int, taus, target_height: int) -> dict:
+    """Blocking curve of 1-SA over the thresholds ``taus`` and the blocking selected by the rule
+    "average block height nearest to ``target_height``".  Returns the library's integer counts per
+    threshold and ``selected`` (index into ``taus``)."""
+    s, keep = _csr_struct(csr, need_vals=False)
+    t = np.ascontiguousarray(taus, dtype=np.float64)
+    out = {k: np.zeros(t.size, dtype=np.int64) for k in ("n_groups", "n_blocks", "stored_elems", "sum_heights")}
+    sel = ctypes.c_int32(0)
+    rc = _lib.sa1_blocking_curve(ctypes.byref(s), int(col_block), t.ctypes.data_as(ctypes.c_void_p), int(t.size),
+                                 int(target_height), *[out[k].ctypes.data_as(ctypes.c_void_p) for k in
+                                                       ("n_groups", "n_blocks", "stored_elems", "sum_heights")],
+                                 ctypes.byref(sel))
+    if rc != 0:
+        raise VbrError(rc, "sa1_blocking_curve")
+    out["selected"] = int(sel.value)
+    out["taus"] = t
+    return out
+
+
+class CsrDev:
+    """Owner of a ``csr_dev_t`` handle: the CSR matrix on the GPU for the comparator kernel."""
+
+    def __init__(self, csr: dict):
+        s, keep = _csr_struct(csr, need_vals=True)
+        h = ctypes.c_void_p()
+        rc = _lib.csr_spmm_create(ctypes.byref(s), ctypes.byref(h))
+        if rc != 0:
+            raise VbrError(rc, "csr_spmm_create")
+        self._h = h
+        self.dtype = csr["dtype"]
+        self.n_rows = int(csr["n_rows"])
+        self._dev = None
+
+    def close(self):
+        if self._h:
+            _lib.csr_free(self._h)
+            self._h = ctypes.c_void_p(None)
+            self._dev = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def upload(self, device="cuda:0"):
+        import torch
+        buf = torch.empty(int(_lib.csr_device_bytes(self._h)), dtype=torch.uint8, device=device)
+        assert buf.data_ptr() % 256 == 0
+        with torch.cuda.device(buf.device):
+            stream = torch.cuda.current_stream().cuda_stream
+            rc = _lib.csr_upload(self._h, ctypes.c_void_p(buf.data_ptr()), ctypes.c_void_p(stream))
+        if rc != 0:
+            raise VbrError(rc, "csr_upload")
+        self._dev = buf
+        return self
+
+    def spmm(self, b, c=None):
+        import torch
+        want = torch.float16 if self.dtype == "f16" else torch.bfloat16
+        if b.dtype != want or b.dim() != 2 or (b.shape[1] > 1 and b.stride(1) != 1):
+            raise ValueError("B must be a 2-D %s tensor with unit column stride" % want)
+        n = b.shape[1]
+        if c is None:
+            c = torch.empty((self.n_rows, n), dtype=torch.float32, device=b.device)
+        with torch.cuda.device(b.device):
+            stream = torch.cuda.current_stream().cuda_stream
+            rc = int(_lib.csr_spmm(self._h, ctypes.c_void_p(b.data_ptr()), int(b.stride(0)), ctypes.c_void_p(c.data_ptr()),
+                                   int(c.stride(0)), int(n), ctypes.c_void_p(stream)))
+        if rc != 0:
+            raise VbrError(rc, "csr_spmm")
+        return c

@@ -311,3 +311,83 @@ extern "C" int sa1_reorder(const vbr_csr_t *csr, int32_t col_block, double tau, 
         return VBR_EINVAL;
     }
 }
+
+namespace vbrk {
+namespace {
+
+// What the VBR matrix of a blocking would hold: per group the number of distinct column blocks
+// its rows touch; a stored block of group g has height h_g.
+void blocking_counts(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups, int32_t G,
+                     int32_t col_block, int64_t *n_blocks, int64_t *stored_elems, int64_t *sum_heights)
+{
+    const int64_t KB = csr->n_cols / col_block;
+    std::vector<int32_t> stamp((size_t)std::max<int64_t>(KB, 1), -1);
+    int64_t nb = 0, stored = 0, sumh = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        const int64_t h = row_groups[g + 1] - row_groups[g];
+        int64_t cnt = 0;
+        for (int64_t q = row_groups[g]; q < row_groups[g + 1]; ++q) {
+            const int64_t r = perm[q];
+            for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                const int64_t j = csr->col_idx[p] / col_block;
+                if (stamp[j] != g) { stamp[j] = g; ++cnt; }
+            }
+        }
+        nb += cnt;
+        stored += cnt * h * col_block;
+        sumh += cnt * h;
+    }
+    *n_blocks = nb;
+    *stored_elems = stored;
+    *sum_heights = sumh;
+}
+
+}  // namespace
+}  // namespace vbrk
+
+extern "C" int sa1_blocking_curve(const vbr_csr_t *csr, int32_t col_block, const double *taus, int32_t n_taus,
+                                  int64_t target_height, int64_t *n_groups, int64_t *n_blocks,
+                                  int64_t *stored_elems, int64_t *sum_heights, int32_t *selected)
+{
+    if (!csr || !taus || n_taus <= 0 || col_block <= 0 || target_height <= 0) return VBR_EINVAL;
+    for (int32_t i = 0; i < n_taus; ++i)
+        if (!(taus[i] >= 0.0 && taus[i] <= 1.0)) return VBR_EINVAL;
+    int rc = vbrk::validate_csr(csr, false);
+    if (rc != VBR_OK) return rc;
+    if (csr->n_cols % col_block != 0) return VBR_EINVAL;
+    try {
+        std::vector<int32_t> perm((size_t)csr->n_rows), rg((size_t)csr->n_rows + 1);
+        int32_t best = 0;
+        bool have = false;
+        unsigned __int128 best_num = 0;    // |sum_heights - target * n_blocks| of the best so far
+        int64_t best_den = 1;              // its n_blocks
+        for (int32_t i = 0; i < n_taus; ++i) {
+            int32_t G = 0;
+            rc = vbrk::sa1_reorder_impl(csr, col_block, taus[i], perm.data(), rg.data(), &G);
+            if (rc != VBR_OK) return rc;
+            int64_t nb, stored, sumh;
+            vbrk::blocking_counts(csr, perm.data(), rg.data(), G, col_block, &nb, &stored, &sumh);
+            if (n_groups) n_groups[i] = G;
+            if (n_blocks) n_blocks[i] = nb;
+            if (stored_elems) stored_elems[i] = stored;
+            if (sum_heights) sum_heights[i] = sumh;
+            if (nb > 0) {
+                // distance of the average block height from the target: |sumh / nb - target|
+                const __int128 diff = (__int128)sumh - (__int128)target_height * nb;
+                const unsigned __int128 num = (unsigned __int128)(diff < 0 ? -diff : diff);
+                if (!have || num * (unsigned __int128)best_den < best_num * (unsigned __int128)nb) {
+                    have = true;
+                    best = i;
+                    best_num = num;
+                    best_den = nb;
+                }
+            }
+        }
+        if (selected) *selected = best;
+        return VBR_OK;
+    } catch (const std::bad_alloc &) {
+        return VBR_ENOMEM;
+    } catch (...) {
+        return VBR_EINVAL;
+    }
+}

@@ -190,12 +190,35 @@ def erdos_renyi(rng, n_rows: int, n_cols: int, density: float, dtype: str = F16)
     return csr_from_coo(n_rows, n_cols, rows, cols, to_bits(_uniform(rng, lin.size), dtype), dtype)
 
 
+def rmat(rng, log2_n: int, avg_degree: float, probs=(0.57, 0.19, 0.19, 0.05), dtype: str = F16,
+         scramble: bool = True) -> dict:
+    """Recursive-matrix graph (section 5.2: generating parameters (0.57, 0.19, 0.19, 0.05)): every
+    edge picks one quadrant per bit of the node index with the given probabilities; duplicate
+    edges collapse.  2^log2_n nodes, about avg_degree entries per row; values U[-1,1]; rows
+    scrambled with a random permutation afterwards (as the paper does before blocking)."""
+    n = 1 << log2_n
+    n_edges = int(round(n * avg_degree))
+    rows = np.zeros(n_edges, dtype=np.int64)
+    cols = np.zeros(n_edges, dtype=np.int64)
+    cum = np.cumsum(probs)
+    for _ in range(log2_n):
+        quad = np.searchsorted(cum, rng.random(n_edges), side="right").clip(0, 3)
+        rows = (rows << 1) | (quad >> 1)
+        cols = (cols << 1) | (quad & 1)
+    lin = np.unique(rows * n + cols)
+    rows = lin // n
+    cols = lin - rows * n
+    a = csr_from_coo(n, n, rows, cols, to_bits(_uniform(rng, lin.size), dtype), dtype)
+    return permute_rows(a, rng.permutation(n)) if scramble else a
+
+
 # ----------------------------------------------------------------------------- the five workloads
-WORKLOADS = ("c1", "c2", "c3", "c4", "c5")
+WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "rmat")
 
 
 def workload(name: str, *, scale: float = 1.0, noise: bool = True, seed: int | None = None) -> dict:
-    """One of the five benchmark workloads (``c1`` .. ``c5``), optionally shrunk.
+    """One of the five benchmark workloads (``c1`` .. ``c5``) or the graph workload ``rmat``,
+    optionally shrunk.
 
     ``scale`` multiplies the matrix dimensions and the dense width N (block sizes, densities and
     value distributions stay), so the small cases keep the structure of the full ones.
@@ -263,4 +286,13 @@ def workload(name: str, *, scale: float = 1.0, noise: bool = True, seed: int | N
         a = erdos_renyi(rng, m, k, 5e-4)
         b = dense_rhs(rng, k, n, F16)
         return dict(name=name, A=a, B=b, N=n, col_block=cb, taus=(0.3,), dtype=F16, info=None)
+    if name == "rmat":
+        # the graph workload of section 6.2: 2^14 nodes, 32 edges per node on average, column
+        # partition of 64, dense width 2^12
+        cb = 64
+        lg = max(8, 14 + int(round(np.log2(scale))))
+        n = sc(4096, 16)
+        a = rmat(rng, lg, 32.0)
+        b = dense_rhs(rng, a["n_cols"], n, F16)
+        return dict(name=name, A=a, B=b, N=n, col_block=cb, taus=(0.4,), dtype=F16, info=None)
     raise ValueError(name)

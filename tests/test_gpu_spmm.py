@@ -112,6 +112,38 @@ def test_short_groups_in_panels_with_split_steps():
     check_c(c, c_ref, s, "tiles and panels mixed")
 
 
+@pytest.mark.parametrize("col_block,n_blocks,density,dtype,n", [(16, 12, 0.03, "f16", 136), (32, 40, 0.01, "bf16", 264),
+                                                              (16, 200, 0.004, "f16", 128)])
+def test_short_groups_wider_blocks_and_padded_leading_dimensions(col_block, n_blocks, density, dtype, n):
+    # thousands of short groups with blocks of 16 and 32 columns (granules of 16 and 32 B rows), few
+    # and many column blocks, B and C with padded leading dimensions
+    rng = np.random.default_rng(col_block + n_blocks)
+    csr = random_csr(rng, 6000, n_blocks * col_block, density, dtype=dtype)
+    b = synth.dense_rhs(rng, n_blocks * col_block, n, dtype)
+    perm, rg = blocking_bit_exact(csr, col_block, 0.9)
+    c, v = gpu_spmm(csr, perm, rg, col_block, b, ldb_pad=8, ldc_pad=4)
+    index_bit_exact(v, csr, perm, rg, col_block)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "short groups cb=%d" % col_block)
+
+
+def test_block_rows_of_exactly_one_slab():
+    # the shape of the pruned-weight workload at a size the oracle multiplies whole: 16 x 16 blocks
+    # kept at 10 %, every block row is one group of exactly one slab
+    rng = np.random.default_rng(31)
+    keep = rng.random((256, 64)) < 0.10
+    mask = np.kron(keep, np.ones((16, 16), dtype=bool))
+    r, cc = np.nonzero(mask)
+    vals = synth.to_bits(rng.standard_normal(r.size).astype(np.float32) / 4, "f16")
+    csr = synth.csr_from_coo(4096, 1024, r, cc, vals, "f16")
+    b = synth.dense_rhs(rng, 1024, 264, "f16", dist="normal")
+    perm, rg = blocking_bit_exact(csr, 16, 0.5)
+    c, v = gpu_spmm(csr, perm, rg, 16, b)
+    index_bit_exact(v, csr, perm, rg, 16)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "block rows of one slab")
+
+
 def test_leading_dimensions_and_overwrite():
     rng = np.random.default_rng(6)
     csr = random_csr(rng, 90, 128, 0.1, dtype="bf16")
@@ -167,6 +199,42 @@ def test_argument_checks_on_the_gpu_entry():
     torch.cuda.synchronize()
 
 
+# --------------------------------------------------------------------------- the CSR comparator kernel
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_csr_comparator_matches_oracle(dtype):
+    import torch
+    rng = np.random.default_rng(21)
+    for m, k, n, dens in [(70, 96, 64, 0.2), (301, 160, 520, 0.05), (33, 64, 8, 0.6), (5, 32, 1032, 0.0)]:
+        csr = random_csr(rng, m, k, dens, dtype=dtype)
+        b_bits = synth.dense_rhs(rng, k, n, dtype)
+        h = binding.CsrDev(csr).upload("cuda:0")
+        full = np.zeros((k, n + 8), dtype=np.uint16)
+        full[:, :n] = b_bits
+        b = torch_io.bits_to_device(full, dtype)[:, :n]                      # padded leading dimension
+        c_full = torch.full((m, n + 4), float("nan"), dtype=torch.float32, device="cuda:0")
+        h.spmm(b, c_full[:, :n])
+        torch.cuda.synchronize()
+        out = c_full.cpu().numpy()
+        assert np.isnan(out[:, n:]).all()
+        c_ref, s = oracle.spmm(csr, b_bits)
+        check_c(out[:, :n].astype(np.float64), c_ref, s, "csr %s m=%d n=%d" % (dtype, m, n))
+
+
+def test_csr_comparator_and_blocked_path_agree_on_the_graph_workload():
+    import torch
+    w = synth.workload("rmat", scale=0.125)
+    a, cb = w["A"], w["col_block"]
+    perm, rg = blocking_bit_exact(a, cb, w["taus"][0])
+    c, v = gpu_spmm(a, perm, rg, cb, w["B"])
+    index_bit_exact(v, a, perm, rg, cb)
+    c_ref, s = oracle.spmm(a, w["B"])
+    check_c(c, c_ref, s, "rmat blocked")
+    b = torch_io.bits_to_device(w["B"], w["dtype"])
+    c2 = binding.CsrDev(a).upload("cuda:0").spmm(b)
+    torch.cuda.synchronize()
+    check_c(c2.cpu().numpy().astype(np.float64), c_ref, s, "rmat csr")
+
+
 # --------------------------------------------------------------------------- the five workloads, reduced
 @pytest.mark.parametrize("name,scale,noise", [("c1", 1.0, True), ("c1", 1.0, False), ("c2", 0.25, True),
                                                ("c2", 0.25, False), ("c3", 0.125, True), ("c4", 0.125, True),
@@ -182,7 +250,7 @@ def test_workloads_reduced_elementwise(name, scale, noise):
 
 
 # --------------------------------------------------------------------------- full sizes, sampled rows
-@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5", "rmat"])
 def test_workloads_full_size_sampled_rows(name):
     w = synth.workload(name)
     a, cb = w["A"], w["col_block"]

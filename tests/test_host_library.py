@@ -165,6 +165,26 @@ def test_empty_rows_and_empty_matrix():
     assert v.index()["n_blocks"] == 0 and v.device_bytes() >= 256
 
 
+def test_graph_workload_reduced_bit_exact():
+    w = synth.workload("rmat", scale=0.125)
+    a = w["A"]
+    assert a["n_rows"] == 2048 and 20 < a["nnz"] / a["n_rows"] < 33      # duplicate edges collapse
+    for tau in (0.2, 0.4):
+        perm, rg = assert_same_blocking(a, w["col_block"], tau)
+    assert_same_index(a, perm, rg, w["col_block"], check_values=False)
+
+
+def test_comparator_handle_checks_its_input():
+    csr = csr_from_rows([[0, 1], [2]], n_cols=4)
+    h = binding.CsrDev(csr)
+    assert binding._lib.csr_device_bytes(h._h) % 256 == 0
+    assert binding._lib.csr_spmm(h._h, 256, 8, 256, 8, 8, 0) == -4       # before upload: state error, no GPU touched
+    bad = dict(csr)
+    bad["col_idx"] = np.array([1, 0, 2], dtype=np.int32)
+    with pytest.raises(binding.VbrError):
+        binding.CsrDev(bad)
+
+
 def test_error_paths():
     csr = csr_from_rows([[0, 1], [2]], n_cols=4)
     with pytest.raises(binding.VbrError):
