@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--clean", action="store_true", help="noise-free variant of c1/c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="only the warm-up and the timed region (what the rocprofv3 summaries under profiles/ are "
+                         "made from): no single-launch, cold-cache, comparator, dense or CPU legs")
     ap.add_argument("--no-csr-baseline", action="store_true",
                     help="skip the CSR comparator kernel (the stand-in for the sparse-library routine)")
     ap.add_argument("--no-dense-baseline", action="store_true",
@@ -52,6 +55,8 @@ def main() -> int:
                     help="also run one plain 256 MiB streaming kernel, out = 2*in (outside the timed region): the known-size "
                          "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
+    if args.timed_only:
+        args.no_cpu_baseline = args.no_csr_baseline = args.no_dense_baseline = True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (row groups shard "
               "without any exchange step, see DESIGN.md)" % args.gpus, file=sys.stderr)
@@ -127,10 +132,13 @@ def main() -> int:
             torch.cuda.synchronize()
             out.append(a0.elapsed_time(a1))
         return out
-    single = time_single(20)
-    flush_buf = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device=dev)
-    cold = time_single(5, flush_buf)
-    del flush_buf
+    if args.timed_only:
+        single, cold = [ms], [float("nan")]
+    else:
+        single = time_single(20)
+        flush_buf = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device=dev)
+        cold = time_single(5, flush_buf)
+        del flush_buf
 
     flops_stored = 2.0 * stored * n
     flops_nnz = 2.0 * a["nnz"] * n
@@ -152,7 +160,7 @@ def main() -> int:
     roofline["ms_per_launch"] = ms
     roofline["algorithmic_flops"] = flops_stored
     roofline["algorithmic_hbm_bytes"] = hbm_min
-    tr = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % args.workload)
+    tr = os.path.join(ROOT, "profiles", "hbm_traffic_%s%s.json" % (args.workload, "_clean" if args.clean else ""))
     if os.path.exists(tr):       # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/)
         try:
             roofline["traffic"] = json.load(open(tr)).get("hbm_bytes_per_launch")
