@@ -116,8 +116,9 @@ int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
  *   C_dev  n_rows x N row-major fp32, leading dimension ldc (elements); OVERWRITTEN (beta = 0),
  *          rows in ORIGINAL row order (the reordering is internal); rows without entries get 0
  * Requires N >= 0, N % 8 == 0, ldb >= N, ldb % 8 == 0, ldc >= N, ldc % 4 == 0, B_dev and C_dev
- * 16-byte aligned (else VBR_EINVAL), and n_cols * ldb * 2 < 4 GiB (B rows are addressed with 32-bit
- * byte offsets; else VBR_EUNSUPPORTED).  Products are exact, sums are fp32 on the matrix units.
+ * 16-byte aligned (else VBR_EINVAL), and ldb < 2^26 (inside a granule of 32 B rows lanes use 32-bit
+ * byte offsets; else VBR_EUNSUPPORTED); B itself may be larger than 4 GiB.  Products are exact, sums
+ * are fp32 on the matrix units.
  * B and C must not overlap each other or the uploaded buffer.
  */
 int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,

@@ -147,7 +147,7 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         const int lg = p.lg_gran;
         const int gmask = (1 << lg) - 1;
         const const_i32_ptr krow = (const_i32_ptr)p.krow + (int64_t)td.ks_begin * (kStepK >> lg);
-        const uint32_t ldb_bytes = (uint32_t)(p.ldb * 2);          // host checked: K * ldb * 2 < 2^32
+        const uint32_t ldb_bytes = (uint32_t)(p.ldb * 2);          // host checked: 32 rows of B span less than 2^32 bytes
         const char *Btile = reinterpret_cast<const char *>(p.B) + (int64_t)n0 * 2;
         const bool tile_fast = lg >= 3 && n0 + kTileN <= p.N;
         uint32_t b_col[4];       // byte offset of this lane's chunk from the tile's first column
@@ -203,7 +203,7 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         auto issue_b = [&](int ks, int slot) {
             const uint32_t sb = smem_base + slot * kPanelBytes + 8 * wave * kRowBytes;
             if (tile_fast && rb0 >= 0) {
-                const char *rowptr = Btile + (uint32_t)rb0 * ldb_bytes;          // scalar
+                const char *rowptr = Btile + (uint64_t)(uint32_t)rb0 * ldb_bytes;          // scalar, 64-bit
 #pragma unroll
                 for (int i = 0; i < 4; ++i) dma16_base(b_lane[i], rowptr, sb + 2 * i * kRowBytes);
             } else {         // narrow blocks, padding rows or column tail: zeros come from the zero page
@@ -442,7 +442,7 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
         auto issue_b = [&](int slot) {
             const uint32_t sb = smem_base + slot * kPPanel + 4 * wave * kPRow;
             if (tile_fast && rb0 >= 0) {
-                dma16_base(b_lane, Btile + (uint32_t)rb0 * ldb_bytes, sb);
+                dma16_base(b_lane, Btile + (uint64_t)(uint32_t)rb0 * ldb_bytes, sb);
             } else {
                 const char *src = (rb0 >= 0 && b_col_ok) ? Btile + (int64_t)(rb0 + (rk & gmask)) * ldb_bytes + b_col : zeros;
                 dma16(src, sb);
@@ -657,7 +657,7 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     if (N < 0 || N % 8 != 0 || N > (int64_t)INT32_MAX - 1024) return VBR_EINVAL;
     if (N == 0 || v->n_rows == 0) return VBR_OK;
     if (!B_dev || !C_dev || ldb < N || ldc < N || ldb % 8 != 0 || ldc % 4 != 0) return VBR_EINVAL;
-    if (v->n_cols * ldb * 2 >= ((int64_t)1 << 32)) return VBR_EUNSUPPORTED;   // B rows are addressed with 32-bit byte offsets
+    if (ldb >= ((int64_t)1 << 26)) return VBR_EUNSUPPORTED;   // a lane's offset inside a 32-row granule of B is 32 bits
     if ((reinterpret_cast<uintptr_t>(B_dev) & 15) != 0 || (reinterpret_cast<uintptr_t>(C_dev) & 15) != 0) return VBR_EINVAL;
     const char *d = static_cast<const char *>(v->dev);
     vbrk::Params p;

@@ -199,6 +199,29 @@ def test_argument_checks_on_the_gpu_entry():
     torch.cuda.synchronize()
 
 
+def test_right_hand_side_larger_than_4_gib():
+    # B is a 256-column window of a 70 000 x 32 776 tensor (4.6 GB): row bases need 64 bits
+    import torch
+    rng = np.random.default_rng(41)
+    k, n, ld = 70000, 256, 32776
+    rows = [sorted(set(rng.integers(0, k, size=40).tolist()) | {0, k - 1}) for _ in range(48)]
+    csr = csr_from_rows(rows, n_cols=k, rng=rng)
+    b_bits = synth.dense_rhs(rng, k, n, "f16")
+    big = torch.zeros((k, ld), dtype=torch.float16, device="cuda:0")
+    b = big[:, 1024:1024 + n]
+    b.copy_(torch_io.bits_to_device(b_bits, "f16"))
+    assert k * ld * 2 > (1 << 32) and b.stride(0) == ld
+    for col_block, perm, rg in [(16, np.arange(48, dtype=np.int32), np.array([0, 16, 48], dtype=np.int32)),
+                                (8, *binding.sa1_reorder(csr, 8, 0.3))]:
+        v = binding.vbr_build(csr, perm, rg, col_block).upload("cuda:0")
+        c = torch.full((48, n), float("nan"), dtype=torch.float32, device="cuda:0")
+        v.spmm(b, c)
+        torch.cuda.synchronize()
+        c_ref, s = oracle.spmm(csr, b_bits)
+        check_c(c.cpu().numpy().astype(np.float64), c_ref, s, "B beyond 4 GiB, cb=%d" % col_block)
+    del big
+
+
 # --------------------------------------------------------------------------- the CSR comparator kernel
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_csr_comparator_matches_oracle(dtype):
