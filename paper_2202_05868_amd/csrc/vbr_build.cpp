@@ -21,7 +21,9 @@ inline int slab_class(int n_slabs)   // kernels exist for 1, 2, 4 and 8 slabs
 // Rows of groups shorter than a slab go into panels when the block width allows the scalar
 // gather path and there are enough of them to give every CU a panel or two (a panel is one long
 // running workgroup per 128 columns; a handful of them would leave most of the chip idle).
-constexpr int kPanelSlabs = 16;
+// 8 slabs per panel: measured against 16, twice the workgroups (two resident per CU) gain more
+// than the B rows shared by fewer slabs cost (noisy planted matrix 271 -> 185 us, others within 2 %).
+constexpr int kPanelSlabs = 8;
 constexpr int64_t kPanelMinRows = 4096;
 inline bool use_panels(int lg_gran, int64_t short_rows) { return lg_gran >= 3 && short_rows >= kPanelMinRows; }
 

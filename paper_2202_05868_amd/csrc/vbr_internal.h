@@ -49,7 +49,7 @@ inline int64_t tile_kstep_stride(int32_t n_rows, int32_t n_slabs)
     return (int64_t)(n_slabs - 1) * kFragElems + (int64_t)rows_last * kStepK;
 }
 
-// One workgroup panel: up to 32 slabs cut from the rows of SHORT row groups (height < 16) in
+// One workgroup panel: a few slabs (8) cut from the rows of SHORT row groups (height < 16) in
 // permuted order, whatever group they belong to, walked over the union of the column blocks of
 // those groups.  A B row panel is loaded once per K-step for all slabs; a slab only multiplies
 // where its own groups store a block (mask bit), its fragment then follows in the value stream.
@@ -93,7 +93,7 @@ struct vbr {
     std::vector<int32_t> tile_of_group_order;   // creation order -> index in `tiles`
     std::vector<uint16_t> vals;          // packed fragments: tiles first, then panels, then 1 KiB of zeros
     // panels: rows of groups of height < 16 (when the block width is a multiple of 8)
-    int32_t panel_slabs = 0;             // slabs per panel (16 or 32); 0 = the matrix has no panels
+    int32_t panel_slabs = 0;             // slabs per panel; 0 = the matrix has no panels
     std::vector<int32_t> prow;           // original row of every panel-region row, in permuted order
     std::vector<int32_t> group_prow;     // [n_groups] first panel-region row of a short group, -1 for tall groups
     std::vector<vbrk::PanelDesc> panels;

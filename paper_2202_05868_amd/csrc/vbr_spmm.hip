@@ -592,7 +592,7 @@ int launch_all(const vbr *v, const Params &p, const PanelParams &pp, hipStream_t
 {
     int rc = VBR_OK;
     if (pp.n_panels > 0)     // the panels first: they are the long-running workgroups
-        rc = launch_panels<DT, 16, 4, 3>(v, pp, stream);
+        rc = launch_panels<DT, 8, 4, 3>(v, pp, stream);
     // several classes, none of which alone gives every CU a couple of workgroups: one mixed launch
     int classes = 0;
     for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];

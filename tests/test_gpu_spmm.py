@@ -86,9 +86,9 @@ def test_result_does_not_depend_on_the_row_partition_used():
         check_c(c, c_ref, s, name)
 
 
-def test_short_groups_in_panels_with_split_steps():
+def test_short_groups_in_panels():
     # more than 4096 rows in groups shorter than a slab: the panel kernel; few column blocks at
-    # high density force K-steps with more present slabs than one step carries (split steps)
+    # high density make nearly every slab present in every K-step (full masks)
     rng = np.random.default_rng(12)
     csr = random_csr(rng, 6000, 12 * 8, 0.08)
     b = synth.dense_rhs(rng, 96, 136, "f16")            # one full 128-column tile + a ragged one

@@ -136,10 +136,10 @@ def test_build_accepts_any_valid_partition_and_tall_groups():
     assert_same_index(csr, np.arange(300, dtype=np.int32), np.array([0, 300], dtype=np.int32), 4)
 
 
-def test_panels_with_split_steps_unpack_exactly():
+def test_panels_unpack_exactly():
     # more than 4096 rows in groups shorter than a slab: they are packed as panels; 12 column
-    # blocks at high density make most K-steps carry more present slabs than one step takes, so
-    # steps are split; every stored block must still unpack bit-exactly
+    # blocks at high density make nearly every slab present in every K-step (full masks); every
+    # stored block must unpack bit-exactly
     rng = np.random.default_rng(77)
     csr = random_csr(rng, 6000, 12 * 8, 0.08)
     perm, rg = assert_same_blocking(csr, 8, 0.9)
