@@ -143,7 +143,6 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     std::vector<uint32_t> blk_mask;            // per union block: slabs that store it
     std::vector<int64_t> frag_of;              // [logical step][slab] -> fragment ordinal in the panel, -1
     std::vector<int64_t> fill_dst, fill_src;   // panel values: position in vals <- position in csr->vals
-    const int64_t tiles_units = a_units;       // panels' values follow the tiles'
     for (int64_t pn = 0; pn < n_panels; ++pn) {
         const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
         // union of blocks, and per block the slabs that hold it
@@ -227,7 +226,6 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     // pass 3: the values.  One allocation: tiles' fragments, panels' fragments, and one fragment
     // of zeros behind the last value (loads that run past a panel's data stay inside, and the
     // panel kernel's filler loads read it).
-    (void)tiles_units;
     v->vals.assign((size_t)a_units * 8 + kFragElems, 0);
     const uint16_t *src = static_cast<const uint16_t *>(csr->vals);
     for (size_t e = 0; e < fill_dst.size(); ++e) v->vals[(size_t)fill_dst[e]] = src[fill_src[e]];

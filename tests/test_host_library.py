@@ -163,6 +163,11 @@ def test_empty_rows_and_empty_matrix():
     assert len(rg) == 2
     v = assert_same_index(empty, perm, rg, 4)
     assert v.index()["n_blocks"] == 0 and v.device_bytes() >= 256
+    none = csr_from_rows([], n_cols=8)                    # no rows at all
+    perm, rg = assert_same_blocking(none, 4, 0.5)
+    assert perm.size == 0 and rg.tolist() == [0]
+    v = binding.vbr_build(none, perm, rg, 4)
+    assert v.index()["n_groups"] == 0 and v.device_bytes() >= 256
 
 
 def test_graph_workload_reduced_bit_exact():
