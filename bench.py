@@ -156,7 +156,11 @@ def main() -> int:
         gbs = hbm_min / (ms * 1e-3) * 1e-9
         roofline = dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
                         traffic=None)
-    roofline["kernel"] = "vbr_spmm_kernel"
+    # the kernel(s) one vbr_spmm call launches for this workload (see profiles/): the time between the
+    # events is the whole call's
+    roofline["kernel"] = {"c4": "vbr_spmm_kernel<f16, 1 slab>", "c3": "vbr_spmm_mixed_kernel", "c1": "vbr_spmm_mixed_kernel",
+                          "c5": "vbr_spmm_panel_kernel", "rmat": "vbr_spmm_panel_kernel + vbr_spmm_mixed_kernel",
+                          "c2": "vbr_spmm_kernel<f16, 4 slabs>" if args.clean else "vbr_spmm_panel_kernel"}[args.workload]
     roofline["ms_per_launch"] = ms
     roofline["algorithmic_flops"] = flops_stored
     roofline["algorithmic_hbm_bytes"] = hbm_min
