@@ -120,6 +120,10 @@ int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
  * byte offsets; else VBR_EUNSUPPORTED); B itself may be larger than 4 GiB.  Products are exact, sums
  * are fp32 on the matrix units.
  * B and C must not overlap each other or the uploaded buffer.
+ * Non-finite values: the zero fill-in of a stored block is multiplied like any other value, so a
+ * NaN or Inf in B row k reaches every C row whose group stores the column block of k (the
+ * format's semantics), and, for groups lower than 16 rows, also the rows of the other low groups
+ * that share their 16-row slab.  B rows of column blocks that no group stores are never read.
  */
 int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,
              int64_t N, void *hip_stream);

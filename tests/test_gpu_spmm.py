@@ -199,6 +199,33 @@ def test_argument_checks_on_the_gpu_entry():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("col_block,short", [(16, False), (8, True), (3, False)])
+def test_b_rows_no_block_touches_never_reach_c(col_block, short):
+    # Column blocks no row of A enters hold NaN and Inf in B.  Padding of K-steps, of partial slabs
+    # and of absent slabs must come from zeros, never from whatever B rows happen to be near: C
+    # stays finite and within the bound.  (B rows inside a STORED block do meet the block's
+    # fill-in zeros: that is the format's semantics, not tested here.)
+    import torch
+    rng = np.random.default_rng(50 + col_block)
+    kb, n = 40, 136
+    m = 6000 if short else 300
+    dens = 0.004 if short else 0.05
+    csr = random_csr(rng, m, kb * col_block, dens)
+    # empty the odd column blocks of A
+    keep = (csr["col_idx"] // col_block) % 2 == 0
+    rows = np.repeat(np.arange(m), np.diff(csr["row_ptr"]))[keep]
+    csr = synth.csr_from_coo(m, kb * col_block, rows, csr["col_idx"][keep], csr["vals"][keep], "f16")
+    b_bits = synth.dense_rhs(rng, kb * col_block, n, "f16")
+    poison = b_bits.copy()
+    odd = (np.arange(kb * col_block) // col_block) % 2 == 1
+    poison[odd] = np.where(rng.random((int(odd.sum()), n)) < 0.5, 0x7E00, 0x7C00).astype(np.uint16)   # NaN / +Inf
+    perm, rg = blocking_bit_exact(csr, col_block, 0.9 if short else 0.4)
+    c, v = gpu_spmm(csr, perm, rg, col_block, poison)
+    c_ref, s = oracle.spmm(csr, b_bits)          # the clean B: A never reads the poisoned rows
+    assert np.isfinite(c).all()
+    check_c(c, c_ref, s, "poisoned B rows, cb=%d" % col_block)
+
+
 def test_right_hand_side_larger_than_4_gib():
     # B is a 256-column window of a 70 000 x 32 776 tensor (4.6 GB): row bases need 64 bits
     import torch
