@@ -299,8 +299,12 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
             __builtin_amdgcn_s_barrier();          // ... and everybody else's; the slots of K-step ks-1 are free
             asm volatile("" ::"s"(rb0));           // the scalar row lookup is waited for here, not behind the LDS reads
             read_frags(bslot, aslot);
+            // the load path is what bounds the kernel: a wave that is about to issue its loads goes
+            // ahead of the waves that are multiplying (measured: 3-4 % on the 16-row workload)
+            __builtin_amdgcn_s_setprio(3);
             issue_b(ks + NS - 1, bslot == 0 ? NS - 1 : bslot - 1);
             issue_a(ks + DA, aslot == 0 ? NAS - 1 : aslot - 1);
+            __builtin_amdgcn_s_setprio(0);
             multiply();
             rb0 = rb1;
             rb1 = load_rows(ks + NS + 1);
