@@ -59,7 +59,7 @@ def main() -> int:
         args.no_cpu_baseline = args.no_csr_baseline = args.no_dense_baseline = True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (row groups shard "
-              "without any exchange step, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "without any exchange step; nothing here uses a second GPU)" % args.gpus, file=sys.stderr)
         return 2
 
     import numpy as np
