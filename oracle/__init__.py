@@ -7,7 +7,8 @@ Nothing in the product package imports this; only the tests, the smoke check and
 Pins (see tests/test_oracle_*.py): brute-force dense products, identity right-hand sides, a
 set-based transcription of the greedy pass on tiny matrices, the pathological example and the
 density bound of section 3.2 of the paper, tau = 1 against a plain unique-rows grouping,
-planted-structure recovery.  No function here is left unpinned.
+planted-structure recovery; the blocking curve against planted height and fill and a numpy
+grouping at tau = 1 (tests/test_blocking_curve.py).  No function here is left unpinned.
 """
 from __future__ import annotations
 
