@@ -226,6 +226,46 @@ def test_b_rows_no_block_touches_never_reach_c(col_block, short):
     check_c(c, c_ref, s, "poisoned B rows, cb=%d" % col_block)
 
 
+def test_runs_on_the_given_stream_and_in_a_captured_graph():
+    # vbr_spmm only enqueues kernels on the stream it is given (no allocation, no memset, no
+    # synchronisation), so it can run on a side stream and be captured into a graph; every replay
+    # must reproduce the eager result for the B that is in place at that moment
+    import torch
+    rng = np.random.default_rng(60)
+    w = synth.workload("c3", scale=0.125)            # tall and low groups: several kernels per call
+    a, cb = w["A"], w["col_block"]
+    perm, rg = binding.sa1_reorder(a, cb, w["taus"][1])
+    v = binding.vbr_build(a, perm, rg, cb).upload("cuda:0")
+    k, n = w["B"].shape
+    b = torch_io.bits_to_device(w["B"], w["dtype"])
+    c_ref, s_ref = oracle.spmm(a, w["B"])
+    side = torch.cuda.Stream()                        # default priority
+    c_side = torch.full((a["n_rows"], n), float("nan"), dtype=torch.float32, device="cuda:0")
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        v.spmm(b, c_side)
+    side.synchronize()
+    check_c(c_side.cpu().numpy().astype(np.float64), c_ref, s_ref, "side stream")
+
+    c_graph = torch.full_like(c_side, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        v.spmm(b, c_graph)
+    for rep in range(3):
+        b_bits = synth.dense_rhs(rng, k, n, w["dtype"], dist="normal")
+        b.copy_(torch_io.bits_to_device(b_bits, w["dtype"]))       # eager work between the replays
+        c_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        c_eager = v.spmm(b, torch.empty_like(c_graph))
+        torch.cuda.synchronize()
+        assert torch.equal(c_graph, c_eager), "replay %d differs from the eager launch" % rep
+        c_ref, s_ref = oracle.spmm(a, b_bits)
+        check_c(c_graph.cpu().numpy().astype(np.float64), c_ref, s_ref, "graph replay %d" % rep)
+
+
 def test_right_hand_side_larger_than_4_gib():
     # B is a 256-column window of a 70 000 x 32 776 tensor (4.6 GB): row bases need 64 bits
     import torch
