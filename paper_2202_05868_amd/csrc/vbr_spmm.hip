@@ -149,7 +149,11 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         const const_i32_ptr krow = (const_i32_ptr)p.krow + (int64_t)td.ks_begin * (kStepK >> lg);
         const uint32_t ldb_bytes = (uint32_t)(p.ldb * 2);          // host checked: 32 rows of B span less than 2^32 bytes
         const char *Btile = reinterpret_cast<const char *>(p.B) + (int64_t)n0 * 2;
-        const bool tile_fast = lg >= 3 && n0 + kTileN <= p.N;
+        // In the last column tile the chunks at or beyond column N do not exist: their lanes fetch
+        // the tile's last existing chunk again (the C columns it would feed are never stored, and
+        // columns do not mix), so the fast path serves partial tiles too.
+        const bool tile_fast = lg >= 3;
+        const int last_chunk = (p.N - n0 < kTileN ? p.N - n0 : kTileN) / 8 - 1;
         uint32_t b_col[4];       // byte offset of this lane's chunk from the tile's first column
         uint32_t b_lane[4];      // fast path: offset of this lane's 16 bytes from the first row of the wave's granule
         bool b_col_ok[4];
@@ -157,8 +161,8 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         for (int i = 0; i < 4; ++i) {
             const int chunk = (lane & 31) ^ (2 * (2 * i + half));
             b_col[i] = chunk * 16;
-            b_col_ok[i] = n0 + chunk * 8 < p.N;
-            b_lane[i] = (uint32_t)((8 * wave + 2 * i + half) & gmask) * ldb_bytes + b_col[i];
+            b_col_ok[i] = chunk <= last_chunk;
+            b_lane[i] = (uint32_t)((8 * wave + 2 * i + half) & gmask) * ldb_bytes + (chunk <= last_chunk ? chunk : last_chunk) * 16;
         }
 
         // ---- A staging.  A direct-to-LDS load costs the CU the same whatever its lane mask, so a
@@ -433,23 +437,22 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
         const_i32_ptr p_rb = meta + 1 + ((4 * wave) >> lg), p_ma = meta, p_mc = meta;
         const uint32_t ldb_bytes = (uint32_t)(p.ldb * 2);
         const char *Btile = reinterpret_cast<const char *>(p.B) + (int64_t)n0 * 2;
-        const bool tile_fast = n0 + kPN <= p.N;
+        // chunks at or beyond column N: their lanes fetch the tile's last existing chunk again
+        // (the C columns it would feed are never stored, and columns do not mix)
+        const int last_chunk = (p.N - n0 < kPN ? p.N - n0 : kPN) / 8 - 1;
         const int rk = 4 * wave + q;                                // this lane's row of the K-step
         const int b_chunk = s16 ^ (2 * (rk & 7));
-        const uint32_t b_col = b_chunk * 16;
-        const bool b_col_ok = n0 + b_chunk * 8 < p.N;
-        const uint32_t b_lane = (uint32_t)(rk & gmask) * ldb_bytes + b_col;
+        const uint32_t b_lane = (uint32_t)(rk & gmask) * ldb_bytes + (b_chunk <= last_chunk ? b_chunk : last_chunk) * 16;
         auto next_rows = [&]() -> int { const int v = *p_rb; p_rb += rec; return v; };
         auto next_ma = [&]() -> uint32_t { const uint32_t v = (uint32_t)*p_ma; p_ma += rec; return v; };
         auto next_mc = [&]() -> uint32_t { const uint32_t v = (uint32_t)*p_mc; p_mc += rec; return v; };
         int rb0, rb1;
         auto issue_b = [&](int slot) {
             const uint32_t sb = smem_base + slot * kPPanel + 4 * wave * kPRow;
-            if (tile_fast && rb0 >= 0) {
+            if (rb0 >= 0) {
                 dma16_base(b_lane, Btile + (uint64_t)(uint32_t)rb0 * ldb_bytes, sb);
-            } else {
-                const char *src = (rb0 >= 0 && b_col_ok) ? Btile + (int64_t)(rb0 + (rk & gmask)) * ldb_bytes + b_col : zeros;
-                dma16(src, sb);
+            } else {         // padding rows of the K-step: zeros
+                dma16(zeros, sb);
             }
         };
         // ---- A staging: the fragments of a K-step follow each other in memory, one per present
