@@ -164,12 +164,13 @@ def main() -> int:
     roofline["ms_per_launch"] = ms
     roofline["algorithmic_flops"] = flops_stored
     roofline["algorithmic_hbm_bytes"] = hbm_min
-    tr = os.path.join(ROOT, "profiles", "hbm_traffic_%s%s.json" % (args.workload, "_clean" if args.clean else ""))
-    if os.path.exists(tr):       # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/)
-        try:
-            roofline["traffic"] = json.load(open(tr)).get("hbm_bytes_per_launch")
-        except Exception:
-            pass
+    # HBM bytes per launch measured with rocprofv3 --pmc: the figure the summary under profiles/ ends with
+    tr = os.path.join(ROOT, "profiles", "vbr_spmm_%s%s.txt" % (args.workload, "_clean" if args.clean else ""))
+    if os.path.exists(tr):
+        import re
+        m = re.search(r"^HBM traffic per launch: ([0-9.]+) MB", open(tr).read(), flags=re.M)
+        if m:
+            roofline["traffic"] = float(m.group(1)) * 1e6
 
     out = {
         "metric": "VBR-SpMM TFLOP/s (stored-block flops 2*stored_elems*N)",
