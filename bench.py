@@ -183,7 +183,8 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": w["dtype"] + " x " + w["dtype"] + " -> f32 (MFMA)",
+        "dtype": w["dtype"],
+        "accumulate_dtype": "f32 (MFMA)",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload] + ("" if not args.clean else " (noise-free)"),
                    "N": n, "col_block": cb, "tau": tau, "parallelism": "1 GPU"},
