@@ -188,6 +188,12 @@ def main() -> int:
     roofline["ms_per_launch"] = ms
     roofline["algorithmic_flops"] = flops_stored
     roofline["algorithmic_hbm_bytes"] = hbm_min
+    # what actually binds row groups of one slab: B rows gathered from the caches into LDS, one panel
+    # per stored block and 256-column tile (sum over blocks of col_block * N * 2 bytes); the measured rate
+    # of direct-to-LDS load instructions allows about 28 TB/s for the chip
+    gathered = float(ix["n_blocks"]) * cb * n * 2
+    roofline["cache_to_lds_gather"] = {"bytes": gathered, "achieved_TBs": gathered / (ms * 1e-3) * 1e-12,
+                                       "load_instruction_bound_TBs": 28.0}
     # HBM bytes per launch measured with rocprofv3 --pmc: the figure the summary under profiles/ ends with
     tr = os.path.join(ROOT, "profiles", "vbr_spmm_%s%s.txt" % (args.workload, "_clean" if args.clean else ""))
     if os.path.exists(tr):
