@@ -144,6 +144,31 @@ def test_block_rows_of_exactly_one_slab():
     check_c(c, c_ref, s, "block rows of one slab")
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_partitions_and_widths(seed):
+    # random everything: size, block width (fast and slow gather paths), density, dtype, dense
+    # width with and without a column tail, padded leading dimensions, and an arbitrary valid row
+    # partition with heights from 1 row to several tiles
+    rng = np.random.default_rng(1000 + seed)
+    col_block = int(rng.choice([1, 2, 4, 5, 8, 12, 16, 24, 32, 48, 64]))
+    kb = int(rng.integers(1, 30))
+    m = int(rng.integers(1, 700))
+    n = 8 * int(rng.integers(1, 80))
+    dtype = "bf16" if seed % 2 else "f16"
+    csr = random_csr(rng, m, kb * col_block, float(rng.choice([0.01, 0.05, 0.3])), dtype=dtype)
+    b = synth.dense_rhs(rng, kb * col_block, n, dtype, dist="normal" if seed % 3 else "uniform")
+    cuts = np.unique(np.concatenate([[0, m], rng.integers(0, m + 1, size=int(rng.integers(0, 12)))]))
+    if rng.random() < 0.4:                     # plus a run of single-row groups
+        lo = int(rng.integers(0, m)); hi = min(m, lo + int(rng.integers(1, 60)))
+        cuts = np.unique(np.concatenate([cuts, np.arange(lo, hi + 1)]))
+    rg = cuts.astype(np.int32)
+    perm = rng.permutation(m).astype(np.int32)
+    c, v = gpu_spmm(csr, perm, rg, col_block, b, ldb_pad=8 * int(rng.integers(0, 3)), ldc_pad=4 * int(rng.integers(0, 3)))
+    index_bit_exact(v, csr, perm, rg, col_block)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "seed %d cb=%d m=%d n=%d groups=%d" % (seed, col_block, m, n, rg.size - 1))
+
+
 def test_leading_dimensions_and_overwrite():
     rng = np.random.default_rng(6)
     csr = random_csr(rng, 90, 128, 0.1, dtype="bf16")
