@@ -31,7 +31,7 @@ WORKLOAD_TEXT = {
     "c3": "configs[2]: A 16384x16384 bf16, heights {16,32,64,128} x 32 blocks at 2%, fill 0.7, N=512, tau=0.6",
     "c4": "configs[3]: pruned-weight-like A 4096x16384 fp16, 16x16 blocks kept at 10%, N=4096, tau=0.5",
     "c5": "configs[4]: Erdos-Renyi A 32768x32768 fp16 density 0.05%, column block 32, N=256, tau=0.3",
-    "rmat": "graph workload of the paper's section 6.2: RMAT (0.57,0.19,0.19,0.05), 2^14 nodes, 32 edges per node, "
+    "rmat": "graph workload of the paper's sections 4.1 / 4.4.3: RMAT (0.57,0.19,0.19,0.05), 2^14 nodes, 32 edges per node, "
             "rows scrambled, column block 64, N=4096, tau=0.4",
 }
 
@@ -234,7 +234,7 @@ def main() -> int:
     }
 
     if not args.no_csr_baseline:
-        # the comparison of the paper's section 6.2: the same product straight from CSR (own kernel,
+        # the comparison of the paper's section 4.4.2: the same product straight from CSR (own kernel,
         # fp32 FMAs on the vector units), timed the same way
         hcsr = binding.CsrDev(a).upload(dev)
         cc = torch.empty_like(c)

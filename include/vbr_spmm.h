@@ -12,7 +12,8 @@
  *   vbr_build     row partition + column partition -> variable-block-row matrix that keeps
  *                 only the nonzero blocks, zero-filled (section 2, section 3.1 last paragraph).
  *   vbr_spmm      C = A.B, every stored block multiplied as a small dense product on the
- *                 matrix units (section 4.4.1), in one kernel launch.
+ *                 matrix units (section 4.4.1), in one launch per kernel class the matrix
+ *                 needs (at most five: see vbr_spmm below).
  *
  * sa1_reorder and vbr_build are deterministic integer host code.  vbr_spmm runs on the GPU.
  * All pointers are HOST pointers unless the name ends in _dev.  Nothing is retained from the
@@ -134,16 +135,16 @@ int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_
 void vbr_free(vbr_t *v);
 
 /*
- * Blocking curve (sections 4.1 and 6.1): run 1-SA once per threshold taus[0 .. n_taus-1] and
+ * Blocking curve (sections 2.2 and 4.3.1): run 1-SA once per threshold taus[0 .. n_taus-1] and
  * report, per threshold, what the VBR matrix of that blocking would hold, without building it:
  *   n_groups[i]       row groups
  *   n_blocks[i]       stored (nonzero) blocks
  *   stored_elems[i]   nonzero area: sum over stored blocks of height * col_block
  *   sum_heights[i]    sum over stored blocks of their height
  * so that the in-block density after blocking is rho' = nnz / stored_elems[i] and the average
- * height of the nonzero blocks is Delta'_H = sum_heights[i] / n_blocks[i] (section 6.1).
+ * height of the nonzero blocks is Delta'_H = sum_heights[i] / n_blocks[i] (section 2.2).
  * *selected is the index of the blocking whose Delta'_H is nearest to target_height (the rule of
- * section 6.2: take the blocking with Delta'_H ~ Delta), compared exactly in integers; of equally
+ * sections 4.3.2 and 4.4.2: take the blocking with Delta'_H ~ Delta), compared exactly in integers; of equally
  * near ones the first in the order given; a blocking without blocks is never selected unless
  * none has any (then 0).  Any out array may be NULL.  target_height > 0.
  */
@@ -154,7 +155,7 @@ int sa1_blocking_curve(const vbr_csr_t *csr, int32_t col_block, const double *ta
 /*
  * Comparator: C = A.B straight from the CSR matrix on the GPU, one fp32 accumulator per output
  * element, no blocking and no matrix units.  It stands where the sparse-library routine stands
- * in the comparison of section 6.2 and is not part of the blocked path.
+ * in the comparison of section 4.4.2 and is not part of the blocked path.
  *   csr_spmm_create   validates the host CSR (canonical form as above) and keeps a copy
  *   csr_device_bytes  device bytes csr_upload needs (multiple of 256, never 0)
  *   csr_upload        copies it into buf_dev (caller-allocated, 256-byte aligned) on hip_stream and waits

@@ -138,10 +138,10 @@ def spmm(csr: dict, b_bits: np.ndarray, rows=None, with_bound: bool = True):
 
 
 def blocking_curve(csr: dict, col_block: int, taus, target_height: int) -> dict:
-    """Blocking curve of section 6.1: for every threshold the blocking of ``sa1`` and, from its
+    """Blocking curve of sections 2.2 and 4.3.1: for every threshold the blocking of ``sa1`` and, from its
     VBR index, the number of nonzero blocks, the nonzero area, the in-block density
     rho' = nnz / area and the average height Delta'_H of the nonzero blocks; ``selected`` is the
-    threshold whose Delta'_H is nearest to ``target_height`` (section 6.2 takes the blocking with
+    threshold whose Delta'_H is nearest to ``target_height`` (sections 4.3.2 and 4.4.2 take the blocking with
     Delta'_H ~ Delta; ties go to the first threshold given, empty blockings are skipped)."""
     from fractions import Fraction
     rows = []

@@ -108,12 +108,38 @@ def sa1_reorder(csr: dict, col_block: int, tau: float):
     return perm, rg[: ng.value + 1].copy()
 
 
+def _check_operands(what: str, dtype: str, n_rows: int, n_cols: int, dev_buf, b, c):
+    """Everything about B and C that the C ABI cannot see (it gets raw addresses): types, shapes,
+    strides and the device they live on.  A short B or C would be read or written out of bounds on
+    the device, so nothing is launched unless these hold.  Returns C (allocated here if None)."""
+    import torch
+    want = torch.float16 if dtype == "f16" else torch.bfloat16
+    if b.dtype != want or b.dim() != 2 or (b.shape[1] > 1 and b.stride(1) != 1):
+        raise ValueError("%s: B must be a 2-D %s tensor with unit column stride" % (what, want))
+    if b.shape[0] < n_cols:
+        raise ValueError("%s: B has %d rows, the matrix has %d columns" % (what, b.shape[0], n_cols))
+    n = b.shape[1]
+    if c is None:
+        c = torch.empty((n_rows, n), dtype=torch.float32, device=b.device)
+    if c.dtype != torch.float32 or c.dim() != 2 or tuple(c.shape) != (n_rows, n) or (n > 1 and c.stride(1) != 1):
+        raise ValueError("%s: C must be a 2-D float32 tensor of shape (%d, %d) with unit column stride" % (what, n_rows, n))
+    if (n_rows > 1 and c.stride(0) < n) or (b.shape[0] > 1 and b.stride(0) < n):
+        raise ValueError("%s: rows of B and C must not overlap (row stride >= N)" % what)
+    if dev_buf is None:
+        raise VbrError(-4, what)
+    if b.device != dev_buf.device or c.device != dev_buf.device:
+        raise ValueError("%s: B and C must be on %s, where the matrix was uploaded" % (what, dev_buf.device))
+    return c
+
+
 class Vbr:
     """Owner of a ``vbr_t`` handle (and, after ``upload``, of the torch tensor behind it)."""
 
-    def __init__(self, handle, dtype: str):
+    def __init__(self, handle, dtype: str, n_rows: int, n_cols: int):
         self._h = ctypes.c_void_p(handle)
         self.dtype = dtype
+        self.n_rows = int(n_rows)
+        self.n_cols = int(n_cols)
         self._dev = None
 
     def close(self):
@@ -182,18 +208,13 @@ class Vbr:
         self._dev = buf
         return self
 
-    def spmm(self, b, c=None, n_rows: int | None = None):
-        """C = A.B.  ``b``: torch [K, N] float16/bfloat16 on the GPU (row stride free, unit column
-        stride); ``c``: optional torch [M, N] float32 output.  Runs on torch's current stream."""
+    def spmm(self, b, c=None):
+        """C = A.B.  ``b``: torch [K, N] float16/bfloat16 on the GPU of the uploaded matrix, K >= the
+        matrix's columns (row stride free, unit column stride); ``c``: optional torch [M, N] float32
+        output on the same GPU.  Runs on torch's current stream."""
         import torch
-        want = torch.float16 if self.dtype == "f16" else torch.bfloat16
-        if b.dtype != want or b.dim() != 2 or (b.shape[1] > 1 and b.stride(1) != 1):
-            raise ValueError("B must be a 2-D %s tensor with unit column stride" % want)
+        c = _check_operands("vbr_spmm", self.dtype, self.n_rows, self.n_cols, self._dev, b, c)
         n = b.shape[1]
-        if c is None:
-            c = torch.empty((n_rows, n), dtype=torch.float32, device=b.device)
-        if c.dtype != torch.float32 or c.dim() != 2 or c.shape[1] != n or (n > 1 and c.stride(1) != 1):
-            raise ValueError("C must be a 2-D float32 tensor with N columns and unit column stride")
         with torch.cuda.device(b.device):
             stream = torch.cuda.current_stream().cuda_stream
             rc = vbr_spmm_raw(self, b.data_ptr(), b.stride(0), c.data_ptr(), c.stride(0), n, stream)
@@ -218,11 +239,11 @@ def vbr_build(csr: dict, perm: np.ndarray, row_groups: np.ndarray, col_block: in
                         ctypes.byref(h))
     if rc != 0:
         raise VbrError(rc, "vbr_build")
-    return Vbr(h.value, csr["dtype"])
+    return Vbr(h.value, csr["dtype"], csr["n_rows"], csr["n_cols"])
 
 
-def vbr_spmm(v: Vbr, b, c=None, n_rows: int | None = None):
-    return v.spmm(b, c, n_rows)
+def vbr_spmm(v: Vbr, b, c=None):
+    return v.spmm(b, c)
 
 
 def sa1_blocking_curve(csr: dict, col_block: int, taus, target_height: int) -> dict:
@@ -256,6 +277,7 @@ class CsrDev:
         self._h = h
         self.dtype = csr["dtype"]
         self.n_rows = int(csr["n_rows"])
+        self.n_cols = int(csr["n_cols"])
         self._dev = None
 
     def close(self):
@@ -284,12 +306,8 @@ class CsrDev:
 
     def spmm(self, b, c=None):
         import torch
-        want = torch.float16 if self.dtype == "f16" else torch.bfloat16
-        if b.dtype != want or b.dim() != 2 or (b.shape[1] > 1 and b.stride(1) != 1):
-            raise ValueError("B must be a 2-D %s tensor with unit column stride" % want)
+        c = _check_operands("csr_spmm", self.dtype, self.n_rows, self.n_cols, self._dev, b, c)
         n = b.shape[1]
-        if c is None:
-            c = torch.empty((self.n_rows, n), dtype=torch.float32, device=b.device)
         with torch.cuda.device(b.device):
             stream = torch.cuda.current_stream().cuda_stream
             rc = int(_lib.csr_spmm(self._h, ctypes.c_void_p(b.data_ptr()), int(b.stride(0)), ctypes.c_void_p(c.data_ptr()),

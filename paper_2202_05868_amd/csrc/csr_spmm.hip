@@ -1,5 +1,5 @@
 // Comparator kernel: C = A.B straight from CSR (the role the sparse-library routine plays in
-// section 6.2 of the paper).  One wave per row and 512-column tile: the lanes hold 8 consecutive
+// section 4.4.2 of the paper).  One wave per row and 512-column tile: the lanes hold 8 consecutive
 // columns each in fp32, the row's entries are walked with wave-uniform (scalar) loads of column
 // index and value, and every entry costs one 16-byte load of B per lane.
 #include <hip/hip_runtime.h>

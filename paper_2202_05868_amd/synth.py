@@ -192,7 +192,7 @@ def erdos_renyi(rng, n_rows: int, n_cols: int, density: float, dtype: str = F16)
 
 def rmat(rng, log2_n: int, avg_degree: float, probs=(0.57, 0.19, 0.19, 0.05), dtype: str = F16,
          scramble: bool = True) -> dict:
-    """Recursive-matrix graph (section 5.2: generating parameters (0.57, 0.19, 0.19, 0.05)): every
+    """Recursive-matrix graph (section 4.1: generating parameters (0.57, 0.19, 0.19, 0.05)): every
     edge picks one quadrant per bit of the node index with the given probabilities; duplicate
     edges collapse.  2^log2_n nodes, about avg_degree entries per row; values U[-1,1]; rows
     scrambled with a random permutation afterwards (as the paper does before blocking)."""
@@ -287,7 +287,7 @@ def workload(name: str, *, scale: float = 1.0, noise: bool = True, seed: int | N
         b = dense_rhs(rng, k, n, F16)
         return dict(name=name, A=a, B=b, N=n, col_block=cb, taus=(0.3,), dtype=F16, info=None)
     if name == "rmat":
-        # the graph workload of section 6.2: 2^14 nodes, 32 edges per node on average, column
+        # the graph workload of sections 4.1 and 4.4.3: 2^14 nodes, 32 edges per node on average, column
         # partition of 64, dense width 2^12
         cb = 64
         lg = max(8, 14 + int(round(np.log2(scale))))

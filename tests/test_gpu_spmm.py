@@ -1,8 +1,8 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle on the same seeded inputs.
 
 Bar: perm, row_groups and the VBR index arrays bit-exact; |C - C_ref| <= 1e-4 * sum_k |a_ik||b_kj|
-elementwise (C_ref and the bound in binary64 from the original CSR).  Small cases are compared
-element by element; the full-size workloads on sampled rows the oracle computes one by one.
+elementwise (C_ref and the bound in binary64 from the original CSR).  Every case, the full-size
+workloads included, is compared element by element.
 """
 import numpy as np
 import pytest
@@ -364,20 +364,54 @@ def test_workloads_reduced_elementwise(name, scale, noise):
         check_c(c, c_ref, s, "%s tau=%g" % (name, tau))
 
 
-# --------------------------------------------------------------------------- full sizes, sampled rows
+# --------------------------------------------------------------------------- wide dense matrices, small A
+def test_one_slab_groups_with_eight_or_more_column_tiles():
+    # N = 2056: nine 256-column tiles (the last one ragged), so the workgroup -> (tile, column
+    # tile) map takes the branch it takes at the full size of the pruned-weight workload
+    rng = np.random.default_rng(77)
+    keep = rng.random((40, 48)) < 0.15
+    mask = np.kron(keep, np.ones((16, 16), dtype=bool))
+    r, cc = np.nonzero(mask)
+    vals = synth.to_bits(rng.standard_normal(r.size).astype(np.float32) / 4, "f16")
+    csr = synth.csr_from_coo(640, 768, r, cc, vals, "f16")
+    b = synth.dense_rhs(rng, 768, 2056, "f16", dist="normal")
+    perm, rg = blocking_bit_exact(csr, 16, 0.5)
+    c, v = gpu_spmm(csr, perm, rg, 16, b)
+    index_bit_exact(v, csr, perm, rg, 16)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "one-slab groups, N=2056")
+
+
+def test_short_groups_with_eight_or_more_column_tiles():
+    # short groups (panels) with N = 1032: nine 128-column tiles, the last one 8 columns wide
+    rng = np.random.default_rng(78)
+    csr = random_csr(rng, 6000, 20 * 16, 0.01)
+    b = synth.dense_rhs(rng, 320, 1032, "f16")
+    perm, rg = blocking_bit_exact(csr, 16, 0.9)
+    h = np.diff(rg)
+    assert h[h < 16].sum() >= 4096
+    c, v = gpu_spmm(csr, perm, rg, 16, b)
+    index_bit_exact(v, csr, perm, rg, 16)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "short groups, N=1032")
+
+
+# --------------------------------------------------------------------------- full sizes, every element
 @pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5", "rmat"])
-def test_workloads_full_size_sampled_rows(name):
+def test_workloads_full_size_every_element(name):
+    # the launch configuration bench.py times, at the full size, every element of C against the
+    # oracle; c3 at all three of its thresholds
     w = synth.workload(name)
     a, cb = w["A"], w["col_block"]
-    tau = w["taus"][len(w["taus"]) // 2]
-    perm, rg = blocking_bit_exact(a, cb, tau)
-    c, v = gpu_spmm(a, perm, rg, cb, w["B"])
-    index_bit_exact(v, a, perm, rg, cb)
-    rng = np.random.default_rng(3)
-    rows = np.unique(np.concatenate([rng.integers(0, a["n_rows"], size=96),
-                                     perm[[0, -1]], [0, a["n_rows"] - 1]]))
-    c_ref, s = oracle.spmm(a, w["B"], rows=rows)
-    check_c(c[rows], c_ref, s, "%s full size, %d sampled rows" % (name, rows.size))
-    # property at any size: rows without entries are exactly zero, nothing is left unwritten
+    print("full size %s: oracle multiply" % name, flush=True)
+    c_ref, s = oracle.spmm(a, w["B"])
     empty = np.nonzero(np.diff(a["row_ptr"]) == 0)[0]
-    assert not np.isnan(c).any() and np.all(c[empty] == 0.0)
+    for tau in w["taus"]:
+        print("full size %s tau=%g: library" % (name, tau), flush=True)
+        perm, rg = blocking_bit_exact(a, cb, tau)
+        c, v = gpu_spmm(a, perm, rg, cb, w["B"])
+        index_bit_exact(v, a, perm, rg, cb)
+        check_c(c, c_ref, s, "%s full size tau=%g" % (name, tau))
+        # rows without entries are exactly zero
+        assert np.all(c[empty] == 0.0)
+        del c, v

@@ -213,3 +213,43 @@ def test_error_paths():
     # spmm before upload: state error, no GPU touched
     assert binding.vbr_spmm_raw(v, 256, 8, 256, 8, 8, 0) == -4
     assert binding._lib.vbr_strerror(-4) == b"call out of order"
+
+
+def test_binding_rejects_operands_the_kernels_would_read_or_write_out_of_bounds():
+    # the C ABI gets raw addresses; shapes, types and the device are checked in the binding,
+    # before anything is launched (CPU tensors suffice: every check precedes the launch)
+    import torch
+    csr = csr_from_rows([[0, 1], [2], [5]], n_cols=8)
+    v = binding.vbr_build(csr, np.arange(3, dtype=np.int32), np.array([0, 3], dtype=np.int32), 2)
+    h = binding.CsrDev(csr)
+    fake_dev = torch.empty(1, dtype=torch.uint8)          # stands for the uploaded buffer (CPU "device")
+    for what, obj in (("vbr_spmm", v), ("csr_spmm", h)):
+        def check(b, c, dev=fake_dev):
+            return binding._check_operands(what, "f16", obj.n_rows, obj.n_cols, dev, b, c)
+        good_b = torch.zeros((8, 16), dtype=torch.float16)
+        good_c = torch.zeros((3, 16), dtype=torch.float32)
+        assert check(good_b, good_c) is good_c
+        assert tuple(check(good_b, None).shape) == (3, 16)
+        for b, c in [(torch.zeros((7, 16), dtype=torch.float16), good_c),            # B too short
+                     (good_b.to(torch.bfloat16), good_c),                            # wrong type
+                     (torch.zeros((16, 8), dtype=torch.float16).t(), good_c),        # column stride
+                     (good_b, torch.zeros((2, 16), dtype=torch.float32)),            # C too short
+                     (good_b, torch.zeros((4, 16), dtype=torch.float32)),            # C too tall
+                     (good_b, torch.zeros((3, 8), dtype=torch.float32)),             # C too narrow
+                     (good_b, torch.zeros((3, 16), dtype=torch.float64)),            # C type
+                     (good_b, torch.zeros((3, 1), dtype=torch.float32).expand(3, 16)),   # C rows overlap
+                     (good_b[:, :8].expand(8, 8)[:, :8].as_strided((8, 8), (0, 1)), torch.zeros((3, 8), dtype=torch.float32))]:
+            with pytest.raises(ValueError):
+                check(b, c)
+        with pytest.raises(binding.VbrError):            # not uploaded
+            check(good_b, good_c, dev=None)
+        if torch.cuda.is_available():
+            with pytest.raises(ValueError):              # uploaded elsewhere than where B and C live
+                check(good_b, good_c, dev=torch.empty(1, dtype=torch.uint8, device="cuda:0"))
+    # through the public methods: shape errors surface before the state error
+    with pytest.raises(ValueError):
+        v.spmm(torch.zeros((4, 16), dtype=torch.float16))
+    with pytest.raises(binding.VbrError):
+        v.spmm(torch.zeros((8, 16), dtype=torch.float16))
+    with pytest.raises(ValueError):
+        h.spmm(torch.zeros((8, 16), dtype=torch.float16), torch.zeros((9, 16), dtype=torch.float32))
