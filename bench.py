@@ -36,6 +36,33 @@ WORKLOAD_TEXT = {
 }
 
 
+def measure_denominators(torch, binding, dev) -> dict:
+    """Rates of the single units the kernels lean on, measured on this GPU with the library's probe
+    loops (HIP events around the third of three launches each): flop/s for the matrix
+    instructions, bytes/s otherwise."""
+    buf = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    iters = {"mfma_16x16x32_f16": 20000, "mfma_16x16x16_f16": 20000, "mfma_32x32x16_f16": 10000,
+             "lds_read_tr_b64": 4000, "lds_read_b64": 4000, "lds_read_b128": 4000, "lds_dma_b128": 2000, "hbm_copy": 1}
+    res = {}
+    for kind, it in iters.items():
+        best = None
+        for _ in range(3):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            work = binding.vbr_probe_launch(kind, buf, it)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3
+            best = t if best is None else min(best, t)
+        res[kind] = {"rate": work / best, "unit": "flop/s" if kind.startswith("mfma") else "B/s", "ms": best * 1e3}
+        if kind.startswith("lds"):
+            res[kind]["bytes_per_clk_per_cu_at_2.4GHz"] = work / best / 256 / 2.4e9
+    del buf
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,12 +81,15 @@ def main() -> int:
                     help="skip the CSR comparator kernel (the stand-in for the sparse-library routine)")
     ap.add_argument("--no-dense-baseline", action="store_true",
                     help="skip the dense product on the zero-filled matrix (run by default for c2 and c4)")
+    ap.add_argument("--no-denominators", action="store_true",
+                    help="skip the measured denominators (matrix-instruction issue rates, LDS operand rates, "
+                         "direct-to-LDS load rate, HBM copy), which run outside the timed region")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB streaming kernel, out = 2*in (outside the timed region): the known-size "
                          "kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.timed_only:
-        args.no_cpu_baseline = args.no_csr_baseline = args.no_dense_baseline = True
+        args.no_cpu_baseline = args.no_csr_baseline = args.no_dense_baseline = args.no_denominators = True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (row groups shard "
               "without any exchange step; nothing here uses a second GPU)" % args.gpus, file=sys.stderr)
@@ -180,27 +210,36 @@ def main() -> int:
         gbs = hbm_min / (ms * 1e-3) * 1e-9
         roofline = dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
                         traffic=None)
-    # the kernel(s) one vbr_spmm call launches for this workload (see profiles/): the time between the
-    # events is the whole call's
-    roofline["kernel"] = {"c4": "vbr_spmm_kernel<f16, 1 slab>", "c3": "vbr_spmm_mixed_kernel", "c1": "vbr_spmm_mixed_kernel",
-                          "c5": "vbr_spmm_panel_kernel", "rmat": "vbr_spmm_panel_kernel + vbr_spmm_mixed_kernel",
-                          "c2": "vbr_spmm_kernel<f16, 4 slabs>" if args.clean else "vbr_spmm_panel_kernel"}[args.workload]
+    # the kernels one vbr_spmm call launches for this workload, from the library's own launch plan;
+    # the time between the events is the whole call's
+    roofline["kernel"] = v.launches(n)
     roofline["ms_per_launch"] = ms
     roofline["algorithmic_flops"] = flops_stored
     roofline["algorithmic_hbm_bytes"] = hbm_min
-    # what actually binds row groups of one slab: B rows gathered from the caches into LDS, one panel
-    # per stored block and 256-column tile (sum over blocks of col_block * N * 2 bytes); the measured rate
-    # of direct-to-LDS load instructions allows about 28 TB/s for the chip
+    # B rows gathered from the caches into LDS when no two row groups share a staged row: one panel
+    # per stored block and column tile (sum over blocks of col_block * N * 2 bytes); priced below
+    # against the measured rate of direct-to-LDS loads
     gathered = float(ix["n_blocks"]) * cb * n * 2
-    roofline["cache_to_lds_gather"] = {"bytes": gathered, "achieved_TBs": gathered / (ms * 1e-3) * 1e-12,
-                                       "load_instruction_bound_TBs": 28.0}
+    roofline["cache_to_lds_gather"] = {"bytes": gathered, "achieved_TBs": gathered / (ms * 1e-3) * 1e-12}
     # HBM bytes per launch measured with rocprofv3 --pmc: the figure the summary under profiles/ ends with
-    tr = os.path.join(ROOT, "profiles", "vbr_spmm_%s%s.txt" % (args.workload, "_clean" if args.clean else ""))
+    tr_name = "vbr_spmm_%s%s.txt" % (args.workload, "_clean" if args.clean else "")
+    tr = os.path.join(ROOT, "profiles", tr_name)
     if os.path.exists(tr):
         import re
         m = re.search(r"^HBM traffic per launch: ([0-9.]+) MB", open(tr).read(), flags=re.M)
         if m:
             roofline["traffic"] = float(m.group(1)) * 1e6
+            roofline["traffic_source"] = "profiles/" + tr_name + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command)"
+
+    # ---- measured denominators (outside the timed region): what the chip delivers per unit
+    denominators = None
+    if not args.no_denominators:
+        denominators = measure_denominators(torch, binding, dev)
+        dma = denominators["lds_dma_b128"]["rate"]
+        roofline["cache_to_lds_gather"]["measured_load_rate_TBs"] = dma * 1e-12
+        roofline["cache_to_lds_gather"]["frac_of_measured_load_rate"] = gathered / (ms * 1e-3) / dma
+        roofline["frac_of_measured_mfma_16x16x32"] = tflops * 1e12 / denominators["mfma_16x16x32_f16"]["rate"]
+        roofline["frac_of_measured_hbm_copy"] = hbm_min / (ms * 1e-3) / denominators["hbm_copy"]["rate"]
 
     out = {
         "metric": "VBR-SpMM TFLOP/s (stored-block flops 2*stored_elems*N)",
@@ -232,6 +271,8 @@ def main() -> int:
         "setup": {"sa1_reorder_s": t1 - t0, "vbr_build_s": t2 - t1, "upload_s": t3 - t2},
         "roofline": roofline,
     }
+    if denominators is not None:
+        out["denominators"] = denominators
 
     if not args.no_csr_baseline:
         # the comparison of the paper's section 4.4.2: the same product straight from CSR (own kernel,

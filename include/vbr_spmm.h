@@ -112,7 +112,8 @@ int64_t vbr_device_bytes(const vbr_t *v);
 int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
 
 /*
- * C = A.B on the GPU (section 4.4.1), asynchronous on hip_stream, no synchronisation.
+ * C = A.B on the GPU (section 4.4.1), asynchronous on hip_stream, no synchronisation; one to
+ * VBR_MAX_LAUNCHES kernel launches (vbr_get_launches lists them), no allocation, no memset.
  *   B_dev  K x N row-major, 16-bit type of the matrix, leading dimension ldb (elements)
  *   C_dev  n_rows x N row-major fp32, leading dimension ldc (elements); OVERWRITTEN (beta = 0),
  *          rows in ORIGINAL row order (the reordering is internal); rows without entries get 0
@@ -128,6 +129,23 @@ int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
  */
 int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,
              int64_t N, void *hip_stream);
+
+/*
+ * The kernel launches one vbr_spmm call with dense width N issues, in issue order (for reporting;
+ * vbr_spmm itself launches from the same plan).  Rows of groups lower than 16 rows are multiplied
+ * by the panel kernel, the other groups by the tile kernel, either in one launch per class of tile
+ * height that occurs (1, 2, 3-4, 5-8 slabs of 16 rows) or, for small matrices, in one launch that
+ * mixes the classes: between 0 and VBR_MAX_LAUNCHES launches.  kinds / tiles / workgroups (each
+ * room for VBR_MAX_LAUNCHES entries, any may be NULL) receive the kernel, the number of row tiles
+ * or panels, and the grid size of each launch.
+ */
+enum { VBR_MAX_LAUNCHES = 5 };
+enum {
+    VBR_LAUNCH_PANEL = 0, VBR_LAUNCH_TILE_1 = 1, VBR_LAUNCH_TILE_2 = 2, VBR_LAUNCH_TILE_4 = 3,
+    VBR_LAUNCH_TILE_8 = 4, VBR_LAUNCH_TILE_MIXED = 5
+};
+int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *kinds, int64_t *tiles,
+                     int64_t *workgroups);
 
 /* Number of workgroup tiles and K-steps of the schedule (for reporting). */
 int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems);
@@ -168,6 +186,33 @@ int csr_upload(csr_dev_t *h, void *buf_dev, void *hip_stream);
 int csr_spmm(const csr_dev_t *h, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,
              int64_t N, void *hip_stream);
 void csr_free(csr_dev_t *h);
+
+/*
+ * Measured denominators (not part of the path; nothing in vbr_spmm calls them): one launch of a
+ * small loop that keeps ONE unit of the compute units busy, at four workgroups of four waves per
+ * compute unit.  The caller times the launch with events on hip_stream; *work receives what one
+ * launch performs (floating-point operations for the VBR_PROBE_MFMA_* kinds, bytes otherwise), so
+ * rate = *work / time.  They price the kernel of section 4.4.1 against what the chip delivers:
+ * the issue rate of the matrix instructions, the rate at which operands leave LDS, the rate of
+ * 16-byte-per-lane direct-to-LDS loads from cache-resident memory, and a copy through HBM.
+ *   buf_dev  caller-allocated device memory, 256-byte aligned, buf_bytes >= 1 MiB; the copy kind
+ *            copies its first half onto its second half; the other kinds only read it, apart from
+ *            a result word at its start that is never actually written
+ *   iters    loop count of the kernel (ignored by VBR_PROBE_HBM_COPY), > 0
+ * VBR_EINVAL for an unknown kind or a bad buffer.  Asynchronous; allocates nothing.
+ */
+enum {
+    VBR_PROBE_MFMA_16X16X32 = 0,   /* v_mfma_f32_16x16x32_f16, 4 independent accumulators per wave */
+    VBR_PROBE_MFMA_16X16X16 = 1,   /* v_mfma_f32_16x16x16_f16 */
+    VBR_PROBE_MFMA_32X32X16 = 2,   /* v_mfma_f32_32x32x16_f16, 2 independent accumulators per wave */
+    VBR_PROBE_LDS_TR_B64 = 3,      /* ds_read_b64_tr_b16 in the kernels' swizzled row pattern */
+    VBR_PROBE_LDS_B64 = 4,         /* ds_read_b64, consecutive addresses */
+    VBR_PROBE_LDS_B128 = 5,        /* ds_read_b128, consecutive addresses */
+    VBR_PROBE_LDS_DMA = 6,         /* global_load_lds_dwordx4 out of a region of at most 2 MiB */
+    VBR_PROBE_HBM_COPY = 7         /* 16 bytes per lane streaming copy */
+};
+int vbr_probe_launch(int32_t kind, void *buf_dev, int64_t buf_bytes, int32_t iters, void *hip_stream,
+                     double *work);
 
 const char *vbr_strerror(int code);
 int vbr_last_hip_error(void);   /* hipError_t of the last failing HIP call on this thread */

@@ -20,7 +20,7 @@ _DTYPES = {"f16": VBR_F16, "bf16": VBR_BF16}
 EXPORTS = ("sa1_reorder", "vbr_build", "vbr_get_index", "vbr_unpack_block", "vbr_device_bytes",
            "vbr_upload", "vbr_spmm", "vbr_get_schedule", "vbr_free", "vbr_strerror",
            "vbr_last_hip_error", "sa1_blocking_curve", "csr_spmm_create", "csr_device_bytes", "csr_upload",
-           "csr_spmm", "csr_free")
+           "csr_spmm", "csr_free", "vbr_probe_launch", "vbr_get_launches")
 
 
 class VbrError(RuntimeError):
@@ -58,6 +58,8 @@ def _load():
     lib.vbr_upload.argtypes = [vp, vp, vp]
     lib.vbr_spmm.argtypes = [vp, vp, i64, vp, i64, i64, vp]
     lib.vbr_get_schedule.argtypes = [vp, P(i64), P(i64), P(i64)]
+    lib.vbr_get_launches.argtypes = [vp, i64, P(i32), vp, vp, vp]
+    lib.vbr_get_launches.restype = ctypes.c_int
     lib.vbr_free.argtypes = [vp]
     lib.vbr_free.restype = None
     lib.vbr_strerror.argtypes = [ctypes.c_int]
@@ -71,6 +73,8 @@ def _load():
     lib.csr_spmm.argtypes = [vp, vp, i64, vp, i64, i64, vp]
     lib.csr_free.argtypes = [vp]
     lib.csr_free.restype = None
+    lib.vbr_probe_launch.argtypes = [i32, vp, i64, i32, vp, P(dbl)]
+    lib.vbr_probe_launch.restype = ctypes.c_int
     for name in ("sa1_reorder", "vbr_build", "vbr_get_index", "vbr_unpack_block", "vbr_upload",
                  "vbr_spmm", "vbr_get_schedule", "sa1_blocking_curve", "csr_spmm_create", "csr_upload", "csr_spmm"):
         getattr(lib, name).restype = ctypes.c_int
@@ -184,6 +188,22 @@ class Vbr:
         if rc != 0:
             raise VbrError(rc, "vbr_get_schedule")
         return dict(n_tiles=a.value, n_ksteps=b.value, packed_elems=c.value)
+
+    LAUNCH_KINDS = ("vbr_spmm_panel_kernel", "vbr_spmm_kernel<1 slab>", "vbr_spmm_kernel<2 slabs>",
+                    "vbr_spmm_kernel<4 slabs>", "vbr_spmm_kernel<8 slabs>", "vbr_spmm_mixed_kernel")
+
+    def launches(self, n: int) -> list:
+        """The kernel launches one ``spmm`` with dense width ``n`` issues, from the library's plan."""
+        kinds = np.zeros(8, dtype=np.int32)
+        tiles = np.zeros(8, dtype=np.int64)
+        wgs = np.zeros(8, dtype=np.int64)
+        cnt = ctypes.c_int32(0)
+        rc = _lib.vbr_get_launches(self._h, int(n), ctypes.byref(cnt), kinds.ctypes.data_as(ctypes.c_void_p),
+                                   tiles.ctypes.data_as(ctypes.c_void_p), wgs.ctypes.data_as(ctypes.c_void_p))
+        if rc != 0:
+            raise VbrError(rc, "vbr_get_launches")
+        return [dict(kernel=self.LAUNCH_KINDS[int(kinds[i])], tiles=int(tiles[i]), workgroups=int(wgs[i]))
+                for i in range(cnt.value)]
 
     def unpack_block(self, blk: int, h: int, col_block: int) -> np.ndarray:
         out = np.empty((h, col_block), dtype=np.uint16)
@@ -315,3 +335,21 @@ class CsrDev:
         if rc != 0:
             raise VbrError(rc, "csr_spmm")
         return c
+
+
+PROBES = {"mfma_16x16x32_f16": 0, "mfma_16x16x16_f16": 1, "mfma_32x32x16_f16": 2, "lds_read_tr_b64": 3,
+          "lds_read_b64": 4, "lds_read_b128": 5, "lds_dma_b128": 6, "hbm_copy": 7}
+
+
+def vbr_probe_launch(kind: str, buf, iters: int) -> float:
+    """Enqueue one launch of a denominator loop on torch's current stream; returns the work (flops
+    or bytes) the launch performs.  ``buf``: a torch uint8 tensor on the GPU (caller-allocated)."""
+    import torch
+    work = ctypes.c_double(0.0)
+    with torch.cuda.device(buf.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = int(_lib.vbr_probe_launch(PROBES[kind], ctypes.c_void_p(buf.data_ptr()), int(buf.numel()), int(iters),
+                                       ctypes.c_void_p(stream), ctypes.byref(work)))
+    if rc != 0:
+        raise VbrError(rc, "vbr_probe_launch")
+    return work.value

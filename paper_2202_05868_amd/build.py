@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvbr_spmm.so")
-SOURCES = ["sa1_reorder.cpp", "vbr_build.cpp", "vbr_spmm.hip", "csr_spmm.hip"]
+SOURCES = ["sa1_reorder.cpp", "vbr_build.cpp", "vbr_spmm.hip", "csr_spmm.hip", "denominators.hip"]
 
 
 def hipcc() -> str:

@@ -558,74 +558,96 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
 }
 
 constexpr int kStages = 2;      // LDS ring of B panels
-
 constexpr int kADistance = 3;   // K-steps the A fragments are requested ahead
 
-template <int DT, int S>
-int launch_class(const vbr *v, const Params &base, int cls, hipStream_t stream)
+// Workgroups of a launch over T row tiles and Q column tiles (see map_workgroup).
+inline int64_t grid_size(int64_t T, int64_t Q)
 {
-    const int T = v->class_begin[cls + 1] - v->class_begin[cls];
-    if (T == 0) return VBR_OK;
-    Params p = base;
-    p.tiles = base.tiles + v->class_begin[cls];
-    p.n_tiles = T;
-    const int64_t Q = p.n_ntiles;
-    int64_t grid;
-    if (Q >= kXcd) grid = (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
-    else grid = (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
-    if (grid > INT32_MAX) return VBR_EINVAL;
-    hipLaunchKernelGGL((vbr_spmm_kernel<DT, S, kStages, kADistance>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
-    return VBR_OK;
+    if (Q >= kXcd) return (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
+    return (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
 }
 
-template <int DT, int R, int NS, int DA>
-int launch_panels(const vbr *v, const PanelParams &pp, hipStream_t stream)
+// The launches one vbr_spmm call issues for dense width N, in issue order: the panels first (they
+// are the long-running workgroups), then either one mixed launch (several slab classes, none of
+// which alone gives every CU a couple of workgroups) or one launch per slab class present.
+struct Launch { int32_t kind; int32_t first_tile, n_tiles; int64_t grid; };
+int plan_launches(const vbr *v, int64_t N, Launch out[VBR_MAX_LAUNCHES])
 {
-    const int64_t T = pp.n_panels, Q = pp.n_ntiles;
-    int64_t grid;
-    if (Q >= kXcd) grid = (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
-    else grid = (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
-    if (grid > INT32_MAX) return VBR_EINVAL;
-    hipLaunchKernelGGL((vbr_spmm_panel_kernel<DT, R, NS, DA>), dim3((unsigned)grid), dim3(kPanelThreads), 0, stream, pp);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
-    return VBR_OK;
-}
-
-template <int DT>
-int launch_all(const vbr *v, const Params &p, const PanelParams &pp, hipStream_t stream)
-{
-    int rc = VBR_OK;
-    if (pp.n_panels > 0)     // the panels first: they are the long-running workgroups
-        rc = launch_panels<DT, 8, 4, 3>(v, pp, stream);
-    // several classes, none of which alone gives every CU a couple of workgroups: one mixed launch
+    int n = 0;
+    const int64_t Qt = (N + kTileN - 1) / kTileN, Qp = (N + 127) / 128;
+    if (!v->panels.empty())
+        out[n++] = Launch{VBR_LAUNCH_PANEL, 0, (int32_t)v->panels.size(), grid_size((int64_t)v->panels.size(), Qp)};
     int classes = 0;
     for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
     const int64_t T_all = v->class_begin[4];
-    if (rc == VBR_OK && classes > 1 && T_all * p.n_ntiles < 4096) {
-        Params pm = p;
-        pm.n_tiles = (int32_t)T_all;
-        const int64_t Q = pm.n_ntiles;
-        const int64_t grid = Q >= kXcd ? (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T_all
-                                        : (int64_t)kXcd * ((T_all + (kXcd / Q) - 1) / (kXcd / Q));
-        hipLaunchKernelGGL((vbr_spmm_mixed_kernel<DT, kStages, kADistance>), dim3((unsigned)grid), dim3(kThreads), 0, stream, pm);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
-        return VBR_OK;
+    if (classes > 1 && T_all * Qt < 4096) {
+        out[n++] = Launch{VBR_LAUNCH_TILE_MIXED, 0, (int32_t)T_all, grid_size(T_all, Qt)};
+        return n;
     }
-    if (rc == VBR_OK) rc = launch_class<DT, 1>(v, p, 0, stream);
-    if (rc == VBR_OK) rc = launch_class<DT, 2>(v, p, 1, stream);
-    if (rc == VBR_OK) rc = launch_class<DT, 4>(v, p, 2, stream);
-    if (rc == VBR_OK) rc = launch_class<DT, 8>(v, p, 3, stream);
-    return rc;
+    for (int c = 0; c < 4; ++c) {
+        const int32_t T = v->class_begin[c + 1] - v->class_begin[c];
+        if (T > 0) out[n++] = Launch{VBR_LAUNCH_TILE_1 + c, v->class_begin[c], T, grid_size(T, Qt)};
+    }
+    return n;
+}
+
+template <int DT>
+int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStream_t stream)
+{
+    Launch plan[VBR_MAX_LAUNCHES];
+    const int n = plan_launches(v, base.N, plan);
+    for (int i = 0; i < n; ++i)
+        if (plan[i].grid > INT32_MAX) return VBR_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        const Launch &L = plan[i];
+        Params p = base;
+        p.tiles = base.tiles + L.first_tile;
+        p.n_tiles = L.n_tiles;
+        const dim3 grid((unsigned)L.grid);
+        switch (L.kind) {
+        case VBR_LAUNCH_PANEL:
+            hipLaunchKernelGGL((vbr_spmm_panel_kernel<DT, 8, 4, 3>), grid, dim3(kPanelThreads), 0, stream, pp);
+            break;
+        case VBR_LAUNCH_TILE_MIXED:
+            hipLaunchKernelGGL((vbr_spmm_mixed_kernel<DT, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        case VBR_LAUNCH_TILE_1:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        case VBR_LAUNCH_TILE_2:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 2, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        case VBR_LAUNCH_TILE_4:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 4, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        default:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 8, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
+    }
+    return VBR_OK;
 }
 
 }  // namespace
 }  // namespace vbrk
 
 extern "C" int vbr_last_hip_error(void) { return vbrk::g_last_hip_error; }
+
+extern "C" int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *kinds, int64_t *tiles, int64_t *workgroups)
+{
+    if (!v || !n_launches || N < 0) return VBR_EINVAL;
+    vbrk::Launch plan[VBR_MAX_LAUNCHES];
+    const int n = (N == 0 || v->n_rows == 0) ? 0 : vbrk::plan_launches(v, N, plan);
+    *n_launches = n;
+    for (int i = 0; i < n; ++i) {
+        if (kinds) kinds[i] = plan[i].kind;
+        if (tiles) tiles[i] = plan[i].n_tiles;
+        if (workgroups) workgroups[i] = plan[i].grid;
+    }
+    return VBR_OK;
+}
 
 extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
 {

@@ -253,3 +253,22 @@ def test_binding_rejects_operands_the_kernels_would_read_or_write_out_of_bounds(
         v.spmm(torch.zeros((8, 16), dtype=torch.float16))
     with pytest.raises(ValueError):
         h.spmm(torch.zeros((8, 16), dtype=torch.float16), torch.zeros((9, 16), dtype=torch.float32))
+
+
+def test_launch_plan_lists_what_a_call_issues():
+    # one-slab groups only: one launch of the one-slab tile kernel, 8 tiles x ceil(N / 256) column tiles
+    rng = np.random.default_rng(3)
+    csr = random_csr(rng, 128, 64, 0.2)
+    v = binding.vbr_build(csr, np.arange(128, dtype=np.int32), np.arange(0, 129, 16, dtype=np.int32), 16)
+    plan = v.launches(4096)
+    assert [p["kernel"] for p in plan] == ["vbr_spmm_kernel<1 slab>"] and plan[0]["tiles"] == 8
+    assert plan[0]["workgroups"] == 8 * 16
+    assert v.launches(0) == []
+    # groups of 16 and of 100 rows: two classes, few tiles -> one mixed launch
+    v = binding.vbr_build(csr, np.arange(128, dtype=np.int32), np.array([0, 16, 116, 128], dtype=np.int32), 16)
+    assert [p["kernel"] for p in v.launches(256)] == ["vbr_spmm_mixed_kernel"]
+    # thousands of short rows: panels first
+    big = random_csr(rng, 6000, 64, 0.05)
+    v = binding.vbr_build(big, np.arange(6000, dtype=np.int32), np.arange(0, 6001, dtype=np.int32), 16)
+    plan = v.launches(256)
+    assert plan[0]["kernel"] == "vbr_spmm_panel_kernel" and plan[0]["tiles"] == (6000 + 127) // 128
