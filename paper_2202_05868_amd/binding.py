@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libvbr_spmm.so")
+LIB_PATH = os.environ.get("VBR_SPMM_LIB") or os.path.join(_HERE, "libvbr_spmm.so")   # the built library; the variable names another build of it
 
 VBR_F16, VBR_BF16 = 0, 1
 _DTYPES = {"f16": VBR_F16, "bf16": VBR_BF16}

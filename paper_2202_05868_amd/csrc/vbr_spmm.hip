@@ -328,7 +328,11 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 const int n = n0 + wave * kWaveN + 16 * f + 4 * q;
-                if (n < p.N) *reinterpret_cast<float4v *>(crow + n) = acc[s][f];
+                if (n >= p.N) continue;
+                // tall tiles store around the caches' write allocation (measured on the dense 4096 x 16384
+                // x 4096 product: 0.44 -> 0.37 ms; no gain, or a small loss, for the lower classes)
+                if constexpr (S >= 8) __builtin_nontemporal_store(acc[s][f], reinterpret_cast<float4v *>(crow + n));
+                else *reinterpret_cast<float4v *>(crow + n) = acc[s][f];
             }
         }
     }
@@ -558,6 +562,8 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
 }
 
 constexpr int kStages = 2;      // LDS ring of B panels
+constexpr int kStagesTall = 3;  // the same for tiles of 5 to 8 slabs (80 KiB of LDS, two workgroups per CU): measured 3 % (K = 16 384)
+                                // to 14 % (K = 8 192) faster than 2 on dense matrices; slower than 2 for every lower class
 constexpr int kADistance = 3;   // K-steps the A fragments are requested ahead
 
 // Workgroups of a launch over T row tiles and Q column tiles (see map_workgroup).
@@ -621,7 +627,7 @@ int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStrea
             hipLaunchKernelGGL((vbr_spmm_kernel<DT, 4, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
             break;
         default:
-            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 8, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 8, kStagesTall, kADistance>), grid, dim3(kThreads), 0, stream, p);
             break;
         }
         const hipError_t e = hipGetLastError();
