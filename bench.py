@@ -81,6 +81,16 @@ def main() -> int:
                     help="skip the CSR comparator kernel (the stand-in for the sparse-library routine)")
     ap.add_argument("--no-dense-baseline", action="store_true",
                     help="skip the dense product on the zero-filled matrix (run by default for c2 and c4)")
+    ap.add_argument("--select-tau", action="store_true",
+                    help="take the threshold from the blocking curve (tau = 0.1 .. 1) by the paper's rule, average block "
+                         "height nearest to the matrix's own block height, instead of the workload's fixed tau")
+    ap.add_argument("--landscape", action="store_true",
+                    help="instead of the benchmark: blocked multiply vs CSR multiply over the synthetic landscape "
+                         "A(Delta, theta, rho) of the paper's Table 2 (section 4.4.2); prints one JSON line")
+    ap.add_argument("--rmat-grid", action="store_true",
+                    help="instead of the benchmark: blocked multiply vs CSR multiply on RMAT graphs, 8 .. 128 edges per "
+                         "node x column blocks 64 / 128 / 256 (section 4.4.3); prints one JSON line")
+    ap.add_argument("--small", action="store_true", help="with --landscape / --rmat-grid: a reduced grid (a minute)")
     ap.add_argument("--no-denominators", action="store_true",
                     help="skip the measured denominators (matrix-instruction issue rates, LDS operand rates, "
                          "direct-to-LDS load rate, HBM copy), which run outside the timed region")
@@ -106,9 +116,34 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.landscape or args.rmat_grid:
+        from paper_2202_05868_amd import experiments
+        say = lambda msg: print(msg, file=sys.stderr, flush=True)
+        if args.landscape:
+            res = (experiments.landscape(n=2048, delta=64, widths=(512, 2048), thetas=(0.1, 0.4), rhos=(0.02, 0.2), progress=say)
+                   if args.small else experiments.landscape(progress=say))
+        else:
+            res = (experiments.rmat_grid(degrees=(8, 64), col_blocks=(64,), log2_nodes=12, width=1024, progress=say)
+                   if args.small else experiments.rmat_grid(progress=say))
+        print(json.dumps(res))
+        return 0
+
     w = synth.workload(args.workload, noise=not args.clean)
     a, cb, n = w["A"], w["col_block"], w["N"]
     tau = w["taus"][len(w["taus"]) // 2]
+    selection = None
+    if args.select_tau:
+        # the matrix's own block height: the planted one, or the column-block width where nothing is planted
+        info = w.get("info")
+        target = int(round(float(np.mean(info["heights"])))) if info else cb
+        taus = [0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0]
+        ts = time.perf_counter()
+        cur = binding.sa1_blocking_curve(a, cb, taus, target)
+        tau = taus[cur["selected"]]
+        selection = {"rule": "average block height nearest to %d" % target, "taus": taus,
+                     "avg_block_height": (cur["sum_heights"] / np.maximum(cur["n_blocks"], 1)).tolist(),
+                     "rho_after": (a["nnz"] / np.maximum(cur["stored_elems"], 1)).tolist(),
+                     "selected_tau": tau, "curve_s": time.perf_counter() - ts}
 
     # ---- one-off host work of the path
     t0 = time.perf_counter()
@@ -268,11 +303,14 @@ def main() -> int:
                      "max_height": int(h.max()) if len(h) else 0, "blocks": int(ix["n_blocks"]),
                      "stored_elems": stored, "nnz": int(a["nnz"]),
                      "fill_overhead": stored / max(1, a["nnz"]), **v.schedule()},
-        "setup": {"sa1_reorder_s": t1 - t0, "vbr_build_s": t2 - t1, "upload_s": t3 - t2},
+        "setup": {"sa1_reorder_s": t1 - t0, "vbr_build_s": t2 - t1, "upload_s": t3 - t2,
+                  "host_threads": os.cpu_count()},
         "roofline": roofline,
     }
     if denominators is not None:
         out["denominators"] = denominators
+    if selection is not None:
+        out["tau_selection"] = selection
 
     if not args.no_csr_baseline:
         # the comparison of the paper's section 4.4.2: the same product straight from CSR (own kernel,

@@ -31,7 +31,7 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
            # packed fp32 instructions are kept out of the generated device code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Xarch_host", "-mpopcnt",
+           "-Xarch_host", "-mpopcnt", "-pthread",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     for s in SOURCES:

@@ -8,7 +8,10 @@
 #include <cstdint>
 #include <cstring>
 #include <new>
+#include <atomic>
+#include <cstdlib>
 #include <numeric>
+#include <thread>
 #include <vector>
 
 #include <immintrin.h>
@@ -64,6 +67,19 @@ int64_t popcount_and_avx512(const uint64_t *a, const uint64_t *b, int64_t w)
 }
 
 typedef int64_t (*popcount_and_fn)(const uint64_t *, const uint64_t *, int64_t);
+
+// Threads of the candidate search that runs ahead of the greedy pass: the host's cores (at most
+// 32), 1 for small inputs; the environment variable VBR_SA1_THREADS overrides the count.
+int scan_threads(int64_t n_classes)
+{
+    if (const char *e = std::getenv("VBR_SA1_THREADS")) {
+        const long v = std::strtol(e, nullptr, 10);
+        if (v >= 1) return (int)std::min<long>(v, 256);
+    }
+    if (n_classes < 4096) return 1;
+    const unsigned hw = std::thread::hardware_concurrency();
+    return (int)std::max(1u, std::min(hw, 32u));
+}
 
 popcount_and_fn pick_popcount_and()
 {
@@ -217,43 +233,31 @@ int sa1_reorder_impl(const vbr_csr_t *csr, int32_t col_block, double tau, int32_
                 for (int64_t w = 0; w < W; ++w)
                     for (uint64_t x = cbits[(size_t)c * W + w]; x; x &= x - 1) inv[fill[(w << 6) + __builtin_ctzll(x)]++] = (int32_t)c;
         }
+        int32_t seed_done = -1;       // the seed being processed: classes up to it are never looked at again
         std::vector<int64_t> first(inv_ptr.begin(), inv_ptr.end() - 1);   // per block: first list entry above the seeds done
         std::vector<int32_t> cnt((size_t)std::max<int64_t>(NC, 1), 0);    // |P & v| of the touched classes
         const int64_t BW = (NC + 63) / 64 + 1;
         std::vector<uint64_t> touched((size_t)BW, 0);
         std::vector<uint64_t> before(W);
-        auto count_list = [&](int64_t b, int32_t above) {                  // classes of block b above `above`
+        // classes of block b above `above` are counted into cnt / touched
+        auto count_list = [&](int64_t b, int32_t above) {
             int64_t &f = first[b];
-            while (f < inv_ptr[b + 1] && inv[f] <= above) ++f;             // classes only rise: skipped for good
-            for (int64_t e = f; e < inv_ptr[b + 1]; ++e) {
+            while (f < inv_ptr[b + 1] && inv[f] <= seed_done) ++f;         // seeds only rise: skipped for good
+            const int64_t lo = above <= seed_done ? f : std::upper_bound(inv.begin() + f, inv.begin() + inv_ptr[b + 1], above) - inv.begin();
+            for (int64_t e = lo; e < inv_ptr[b + 1]; ++e) {
                 const int32_t c = inv[e];
                 ++cnt[c];
                 touched[c >> 6] |= 1ull << (c & 63);
             }
         };
-        for (int32_t seed = 0; seed < NC; ++seed) {
-            if (group_of[seed] != -1) continue;
-            group_of[seed] = G;
-            std::memcpy(P.data(), &cbits[(size_t)seed * W], (size_t)W * 8);
-            sizeP = clen[seed];
-            lam_max = (int64_t)std::floor((double)sizeP / (1.0 - 0.5 * tau));
-            // dense patterns make the lists long: when walking them costs more than comparing
-            // bitsets with every later class, do that instead (same decisions either way)
-            int64_t list_work = 0;
+        // The rest of a seed's pass from class `pos` on (pos itself is done), with the group's
+        // pattern P as it stands: the classes above pos that share a block with P are counted,
+        // visited in rising order, and merged where the condition holds; a merge counts in the tails
+        // of the lists of the blocks it adds.
+        auto scan_from = [&](int32_t pos) {
             for (int64_t w = 0; w < W; ++w)
-                for (uint64_t x = P[w]; x; x &= x - 1) {
-                    const int64_t b = (w << 6) + __builtin_ctzll(x);
-                    list_work += inv_ptr[b + 1] - first[b];
-                }
-            if (list_work > 4 * W * (NC - seed)) {
-                for (int32_t j = seed + 1; j < NC; ++j)
-                    if (group_of[j] == -1 && try_merge(j)) group_of[j] = G;
-                ++G;
-                continue;
-            }
-            for (int64_t w = 0; w < W; ++w)
-                for (uint64_t x = P[w]; x; x &= x - 1) count_list((w << 6) + __builtin_ctzll(x), seed);
-            for (int64_t tw = seed >> 6; tw < BW; ++tw) {
+                for (uint64_t x = P[w]; x; x &= x - 1) count_list((w << 6) + __builtin_ctzll(x), pos);
+            for (int64_t tw = pos >> 6; tw < BW; ++tw) {
                 while (touched[tw]) {
                     const int32_t j = (int32_t)((tw << 6) + __builtin_ctzll(touched[tw]));
                     touched[tw] &= touched[tw] - 1;
@@ -279,7 +283,117 @@ int sa1_reorder_impl(const vbr_csr_t *csr, int32_t col_block, double tau, int32_
                         }
                 }
             }
-            ++G;
+        };
+        // dense patterns make the lists long: when walking them costs more than comparing bitsets
+        // with every later class, a seed does that instead (same decisions either way)
+        auto lists_too_long = [&](const uint64_t *pat, int32_t seed) -> bool {
+            int64_t list_work = 0;
+            for (int64_t w = 0; w < W; ++w)
+                for (uint64_t x = pat[w]; x; x &= x - 1) {
+                    const int64_t b = (w << 6) + __builtin_ctzll(x);
+                    list_work += inv_ptr[b + 1] - first[b];
+                }
+            return list_work > 4 * W * (NC - seed);
+        };
+        auto start_group = [&](int32_t seed) {
+            group_of[seed] = G;
+            std::memcpy(P.data(), &cbits[(size_t)seed * W], (size_t)W * 8);
+            sizeP = clen[seed];
+            lam_max = (int64_t)std::floor((double)sizeP / (1.0 - 0.5 * tau));
+        };
+
+        const int n_threads = scan_threads(NC);
+        if (n_threads <= 1) {
+            for (int32_t seed = 0; seed < NC; ++seed) {
+                if (group_of[seed] != -1) continue;
+                seed_done = seed;
+                start_group(seed);
+                if (lists_too_long(P.data(), seed)) {
+                    for (int32_t j = seed + 1; j < NC; ++j)
+                        if (group_of[j] == -1 && try_merge(j)) group_of[j] = G;
+                } else {
+                    scan_from(seed);
+                }
+                ++G;
+            }
+        } else {
+            // Several threads.  The greedy pass itself stays sequential; what runs ahead of it, for a
+            // batch of possible seeds at a time, is the search that costs the time when few rows
+            // merge: for every class of the batch, the later classes that pass the merge test against
+            // its OWN pattern (the group's pattern until its first merge), in rising order.  The
+            // sequential pass then takes, for a class that is still ungrouped when its turn comes, the
+            // first of those that is still ungrouped, merges it, and finishes that seed's scan from
+            // there with the grown pattern as above.  Classes that do not pass against the seed's
+            // own pattern cannot pass before the first merge, so the decisions, their order and the
+            // groups are those of the one-thread pass.
+            const int32_t batch = (int32_t)std::min<int64_t>(NC, (int64_t)n_threads * 512);
+            std::vector<std::vector<int32_t>> passing((size_t)batch);
+            std::vector<uint8_t> long_lists((size_t)batch, 0);
+            for (int32_t b0 = 0; b0 < NC; b0 += batch) {
+                const int32_t b1 = (int32_t)std::min<int64_t>(NC, (int64_t)b0 + batch);
+                std::atomic<int32_t> next(b0);
+                auto worker = [&]() {
+                    std::vector<int32_t> my_cnt((size_t)NC, 0), hit;
+                    for (;;) {
+                        const int32_t c0 = next.fetch_add(16);
+                        if (c0 >= b1) break;
+                        for (int32_t seed = c0; seed < std::min(b1, c0 + 16); ++seed) {
+                            std::vector<int32_t> &out = passing[(size_t)(seed - b0)];
+                            out.clear();
+                            long_lists[(size_t)(seed - b0)] = 0;
+                            if (group_of[seed] != -1) continue;          // grouped before this batch began
+                            const uint64_t *pat = &cbits[(size_t)seed * W];
+                            if (lists_too_long(pat, seed)) { long_lists[(size_t)(seed - b0)] = 1; continue; }
+                            hit.clear();
+                            for (int64_t w = 0; w < W; ++w)
+                                for (uint64_t x = pat[w]; x; x &= x - 1) {
+                                    const int64_t b = (w << 6) + __builtin_ctzll(x);
+                                    for (int64_t e = std::upper_bound(inv.begin() + inv_ptr[b], inv.begin() + inv_ptr[b + 1], seed) - inv.begin();
+                                         e < inv_ptr[b + 1]; ++e) {
+                                        const int32_t c = inv[e];
+                                        if (my_cnt[c]++ == 0) hit.push_back(c);
+                                    }
+                                }
+                            const int64_t sp = clen[seed];
+                            const int64_t lim = (int64_t)std::floor((double)sp / (1.0 - 0.5 * tau));
+                            for (const int32_t c : hit) {
+                                const int64_t I = my_cnt[c];
+                                my_cnt[c] = 0;
+                                const int64_t U = sp + clen[c] - I;
+                                if (I >= need[U] && U <= lim) out.push_back(c);
+                            }
+                            std::sort(out.begin(), out.end());
+                        }
+                    }
+                };
+                std::vector<std::thread> pool;
+                for (int t = 1; t < n_threads; ++t) pool.emplace_back(worker);
+                worker();
+                for (std::thread &t : pool) t.join();
+
+                for (int32_t seed = b0; seed < b1; ++seed) {
+                    if (group_of[seed] != -1) continue;
+                    seed_done = seed;
+                    start_group(seed);
+                    if (long_lists[(size_t)(seed - b0)]) {
+                        for (int32_t j = seed + 1; j < NC; ++j)
+                            if (group_of[j] == -1 && try_merge(j)) group_of[j] = G;
+                    } else {
+                        for (const int32_t j : passing[(size_t)(seed - b0)]) {
+                            if (group_of[j] != -1) continue;
+                            // the first class that passes and is still free: merge it, then go on from there
+                            const uint64_t *v = &cbits[(size_t)j * W];
+                            int64_t U = 0;
+                            for (int64_t w = 0; w < W; ++w) { P[w] |= v[w]; U += __builtin_popcountll(P[w]); }
+                            sizeP = U;
+                            group_of[j] = G;
+                            scan_from(j);
+                            break;
+                        }
+                    }
+                    ++G;
+                }
+            }
         }
     }
 

@@ -212,17 +212,51 @@ def rmat(rng, log2_n: int, avg_degree: float, probs=(0.57, 0.19, 0.19, 0.05), dt
     return permute_rows(a, rng.permutation(n)) if scramble else a
 
 
+def landscape(rng, n: int, delta: int, theta: float, rho: float, dtype: str = F16, scramble: bool = True) -> dict:
+    """Synthetic blocked matrix A(Delta, theta, rho) of section 4.1: the n x n matrix is divided into
+    Delta x Delta blocks, a fraction theta of ALL blocks (drawn over the whole grid, so block rows
+    differ in how many they hold) is flagged nonzero, and inside every flagged block a fraction rho of
+    the entries is kept (at least one); values U[-1,1].  The rows are scrambled afterwards (section 4.3.1)."""
+    g = n // delta
+    assert g * delta == n
+    n_flag = max(1, int(round(theta * g * g)))
+    flagged = rng.choice(g * g, size=n_flag, replace=False)
+    per = max(1, int(round(rho * delta * delta)))
+    rr, cc = [], []
+    cell = delta * delta
+    for start in range(0, n_flag, 4096):                      # in slices, to bound the scratch memory
+        blk = flagged[start:start + 4096]
+        # per block `per` distinct cells: the smallest `per` of a random key per cell
+        if per * 4 >= cell:
+            keys = rng.random((blk.size, cell))
+            pick = np.argpartition(keys, per - 1, axis=1)[:, :per]
+        else:
+            pick = np.stack([rng.choice(cell, size=per, replace=False) for _ in range(blk.size)])
+        bi = np.repeat(blk // g, per)
+        bj = np.repeat(blk % g, per)
+        e = pick.reshape(-1)
+        rr.append(bi * delta + e // delta)
+        cc.append(bj * delta + e % delta)
+    rows = np.concatenate(rr)
+    cols = np.concatenate(cc)
+    a = csr_from_coo(n, n, rows, cols, to_bits(_uniform(rng, rows.size), dtype), dtype)
+    return permute_rows(a, rng.permutation(n)) if scramble else a
+
+
 # ----------------------------------------------------------------------------- the five workloads
 WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "rmat")
 
 
-def workload(name: str, *, scale: float = 1.0, noise: bool = True, seed: int | None = None) -> dict:
+def workload(name: str, *, scale: float = 1.0, noise: bool = True, seed: int | None = None,
+             rmat_degree: float = 32.0, rmat_col_block: int = 64) -> dict:
     """One of the five benchmark workloads (``c1`` .. ``c5``) or the graph workload ``rmat``,
     optionally shrunk.
 
     ``scale`` multiplies the matrix dimensions and the dense width N (block sizes, densities and
     value distributions stay), so the small cases keep the structure of the full ones.
     ``noise=False`` drops the extra random nonzeros of c1/c2 (the noise-free variant).
+    ``rmat_degree`` / ``rmat_col_block``: edges drawn per node and column-block width of ``rmat``
+    (the paper's grid: 8 .. 128 and 64, 128, 256; section 4.1 and section 4.4.3).
 
     Returns dict(name, A=csr, B=bits[K,N], N, col_block, taus, dtype, info).
     """
@@ -289,10 +323,10 @@ def workload(name: str, *, scale: float = 1.0, noise: bool = True, seed: int | N
     if name == "rmat":
         # the graph workload of sections 4.1 and 4.4.3: 2^14 nodes, 32 edges per node on average, column
         # partition of 64, dense width 2^12
-        cb = 64
+        cb = int(rmat_col_block)
         lg = max(8, 14 + int(round(np.log2(scale))))
         n = sc(4096, 16)
-        a = rmat(rng, lg, 32.0)
+        a = rmat(rng, lg, float(rmat_degree))
         b = dense_rhs(rng, a["n_cols"], n, F16)
         return dict(name=name, A=a, B=b, N=n, col_block=cb, taus=(0.4,), dtype=F16, info=None)
     raise ValueError(name)

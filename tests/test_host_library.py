@@ -109,6 +109,35 @@ def test_reorder_at_sizes_where_both_scan_strategies_run(n_rows, n_blocks, densi
         check_partition_shape(perm, rg, n_rows)
 
 
+@pytest.mark.parametrize("threads", ["1", "3", "8"])
+@pytest.mark.parametrize("n_rows,n_blocks,density", [(3000, 600, 0.004), (3000, 600, 0.02), (2500, 40, 0.5),
+                                                     (2000, 130, 0.08)])
+def test_reorder_with_several_host_threads_is_the_sequential_result(monkeypatch, threads, n_rows, n_blocks, density):
+    # the candidate search that runs ahead of the greedy pass on several threads must not change
+    # a single decision: same inputs as above (merges, refusals and the size cap all occur), the
+    # thread count forced through the environment, compared with the oracle
+    monkeypatch.setenv("VBR_SA1_THREADS", threads)
+    rng = np.random.default_rng(n_rows + n_blocks)
+    base = rng.random((300, n_blocks)) < density
+    rows = []
+    for i in range(n_rows):
+        pat = base[rng.integers(0, 300)] ^ (rng.random(n_blocks) < density * 0.15)
+        rows.append((np.nonzero(pat)[0] * 2 + rng.integers(0, 2)).tolist())
+    csr = csr_from_rows(rows, n_cols=2 * n_blocks, rng=rng)
+    for tau in (0.05, 0.3, 0.6, 0.9, 1.0):
+        perm, rg = assert_same_blocking(csr, 2, tau)
+        check_partition_shape(perm, rg, n_rows)
+
+
+def test_reorder_threads_on_the_unstructured_workload_reduced(monkeypatch):
+    # the workload the parallel search is for: Erdos-Renyi rows, next to no merges
+    w = synth.workload("c5", scale=0.25)
+    for threads in ("1", "4"):
+        monkeypatch.setenv("VBR_SA1_THREADS", threads)
+        for tau in (0.1, 0.3):
+            assert_same_blocking(w["A"], w["col_block"], tau)
+
+
 @pytest.mark.parametrize("name,scale,noise", [("c1", 1.0, True), ("c1", 1.0, False), ("c2", 0.25, True),
                                                ("c3", 0.125, True), ("c4", 0.125, True), ("c5", 0.0625, True)])
 def test_workloads_small_scale_bit_exact(name, scale, noise):
