@@ -99,6 +99,14 @@ int vbr_get_index(const vbr_t *v, const int32_t **row_groups, const int32_t **pe
 /* Copy stored block `blk` out of the packed kernel layout: dst[h_g * col_block] 16-bit, row-major. */
 int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst);
 
+/*
+ * Check of a built matrix against itself: every index the kernels use (B rows of the gather lists,
+ * value offsets of tiles and panels, row positions, the schedule's class ranges, the sections of the
+ * device buffer) lies inside what it indexes.  VBR_OK, or VBR_EINVAL at the first violation.  vbr_build
+ * produces matrices that pass; the tests call this on every matrix they build.
+ */
+int vbr_audit(const vbr_t *v);
+
 /* Bytes of device memory vbr_upload needs (a multiple of 256, never 0). */
 int64_t vbr_device_bytes(const vbr_t *v);
 

@@ -20,7 +20,7 @@ _DTYPES = {"f16": VBR_F16, "bf16": VBR_BF16}
 EXPORTS = ("sa1_reorder", "vbr_build", "vbr_get_index", "vbr_unpack_block", "vbr_device_bytes",
            "vbr_upload", "vbr_spmm", "vbr_get_schedule", "vbr_free", "vbr_strerror",
            "vbr_last_hip_error", "sa1_blocking_curve", "csr_spmm_create", "csr_device_bytes", "csr_upload",
-           "csr_spmm", "csr_free", "vbr_probe_launch", "vbr_get_launches")
+           "csr_spmm", "csr_free", "vbr_probe_launch", "vbr_get_launches", "vbr_audit")
 
 
 class VbrError(RuntimeError):
@@ -60,6 +60,8 @@ def _load():
     lib.vbr_get_schedule.argtypes = [vp, P(i64), P(i64), P(i64)]
     lib.vbr_get_launches.argtypes = [vp, i64, P(i32), vp, vp, vp]
     lib.vbr_get_launches.restype = ctypes.c_int
+    lib.vbr_audit.argtypes = [vp]
+    lib.vbr_audit.restype = ctypes.c_int
     lib.vbr_free.argtypes = [vp]
     lib.vbr_free.restype = None
     lib.vbr_strerror.argtypes = [ctypes.c_int]
@@ -211,6 +213,12 @@ class Vbr:
         if rc != 0:
             raise VbrError(rc, "vbr_unpack_block")
         return out
+
+    def audit(self) -> None:
+        """Raise unless every index the kernels use lies inside what it indexes."""
+        rc = _lib.vbr_audit(self._h)
+        if rc != 0:
+            raise VbrError(rc, "vbr_audit")
 
     def device_bytes(self) -> int:
         return int(_lib.vbr_device_bytes(self._h))

@@ -387,7 +387,129 @@ extern "C" int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst_)
     return VBR_OK;
 }
 
+// Everything the kernels index with, checked against the sizes of what they index into: a wrong
+// entry here would be a device access out of bounds, so the check is plain and complete.
+extern "C" int vbr_audit(const vbr_t *v)
+{
+    using namespace vbrk;
+    if (!v) return VBR_EINVAL;
+    const int64_t M = v->n_rows, K = v->n_cols;
+    const int gran = 1 << v->lg_gran, per_step = kStepK >> v->lg_gran;
+    const int64_t n_vals = (int64_t)v->vals.size();
+    if (n_vals < kFragElems || (int64_t)v->perm.size() != M) return VBR_EINVAL;
+    for (int64_t i = 0; i < M; ++i)
+        if (v->perm[i] < 0 || v->perm[i] >= M) return VBR_EINVAL;
+    for (const int32_t e : v->krow)
+        if (e < -1 || (e >= 0 && (int64_t)e + gran > K)) return VBR_EINVAL;
+    if ((int64_t)v->krow.size() % per_step != 0) return VBR_EINVAL;
+    const int64_t total_ks = (int64_t)v->krow.size() / per_step;
+    if (v->class_begin[0] != 0 || v->class_begin[4] != (int32_t)v->tiles.size()) return VBR_EINVAL;
+    for (int c = 0; c < 4; ++c) {
+        if (v->class_begin[c + 1] < v->class_begin[c]) return VBR_EINVAL;
+        for (int32_t t = v->class_begin[c]; t < v->class_begin[c + 1]; ++t) {
+            const TileDesc &td = v->tiles[t];
+            if (td.n_rows < 1 || td.n_slabs != (td.n_rows + kSlabRows - 1) / kSlabRows || td.n_slabs > kMaxSlabs) return VBR_EINVAL;
+            if (slab_class(td.n_slabs) != c) return VBR_EINVAL;
+            if (td.row_begin < 0 || (int64_t)td.row_begin + td.n_rows > M) return VBR_EINVAL;
+            if (td.n_ks < 0 || td.ks_begin < 0 || (int64_t)td.ks_begin + td.n_ks > total_ks) return VBR_EINVAL;
+            // the fragments of all its K-steps lie inside the values (the zero fragment at the end excluded)
+            if (td.a_off < 0 || td.a_off * 8 + (int64_t)td.n_ks * tile_kstep_stride(td.n_rows, td.n_slabs) > n_vals - kFragElems) return VBR_EINVAL;
+        }
+    }
+    const int rec = 1 + per_step;
+    if ((int64_t)v->pk_meta.size() % rec != 0) return VBR_EINVAL;
+    const int64_t n_rec = (int64_t)v->pk_meta.size() / rec;
+    for (int64_t r = 0; r < n_rec; ++r) {
+        if ((uint32_t)v->pk_meta[r * rec] >> kPanelSlabs) return VBR_EINVAL;                 // mask of at most 8 slabs
+        for (int e = 0; e < per_step; ++e) {
+            const int32_t row = v->pk_meta[r * rec + 1 + e];
+            if (row < -1 || (row >= 0 && (int64_t)row + gran > K)) return VBR_EINVAL;
+        }
+    }
+    for (const int32_t r : v->prow)
+        if (r < 0 || r >= M) return VBR_EINVAL;
+    for (const PanelDesc &pd : v->panels) {
+        if (pd.n_rows < 1 || pd.n_rows > kPanelSlabs * kSlabRows) return VBR_EINVAL;
+        if (pd.row_begin < 0 || (int64_t)pd.row_begin + pd.n_rows > (int64_t)v->prow.size()) return VBR_EINVAL;
+        if (pd.n_ks < 0 || pd.meta_begin < 0) return VBR_EINVAL;
+        if (pd.n_ks > 0 && (int64_t)pd.meta_begin + pd.n_ks + kPanelMetaPad > n_rec) return VBR_EINVAL;
+        int64_t frags = 0;
+        for (int32_t k = 0; k < pd.n_ks; ++k) {
+            const uint32_t m = (uint32_t)v->pk_meta[((int64_t)pd.meta_begin + k) * rec];
+            const int cnt = __builtin_popcount(m);
+            if (cnt < 1 || cnt > kPanelMaxFrags) return VBR_EINVAL;
+            frags += cnt;
+        }
+        for (int32_t k = pd.n_ks; k < pd.n_ks + (pd.n_ks > 0 ? kPanelMetaPad : 0); ++k)
+            if (v->pk_meta[((int64_t)pd.meta_begin + k) * rec] != 0) return VBR_EINVAL;      // look-ahead records carry no slab
+        if (pd.a_off < 0 || pd.a_off * 8 + frags * kFragElems > n_vals - kFragElems) return VBR_EINVAL;
+    }
+    for (size_t i = v->vals.size() - kFragElems; i < v->vals.size(); ++i)
+        if (v->vals[i] != 0) return VBR_EINVAL;                                               // the zero fragment
+    const DeviceLayout &L = v->lay;
+    const int64_t ends[8] = {L.zeros_off + 256, L.tiles_off + (int64_t)v->tiles.size() * (int64_t)sizeof(TileDesc),
+                             L.krow_off + (int64_t)v->krow.size() * 4, L.perm_off + M * 4,
+                             L.panels_off + (int64_t)v->panels.size() * (int64_t)sizeof(PanelDesc),
+                             L.pk_meta_off + (int64_t)v->pk_meta.size() * 4, L.prow_off + (int64_t)v->prow.size() * 4,
+                             L.vals_off + n_vals * 2};
+    const int64_t begins[8] = {L.zeros_off, L.tiles_off, L.krow_off, L.perm_off, L.panels_off, L.pk_meta_off, L.prow_off, L.vals_off};
+    for (int i = 0; i < 8; ++i) {
+        if (begins[i] % 256 != 0 || ends[i] > L.total) return VBR_EINVAL;
+        if (i + 1 < 8 && ends[i] > begins[i + 1]) return VBR_EINVAL;                          // sections in this order, disjoint
+    }
+    return VBR_OK;
+}
+
 extern "C" int64_t vbr_device_bytes(const vbr_t *v) { return v ? v->lay.total : 0; }
+
+namespace vbrk {
+
+// Workgroups of a launch over T row tiles and Q column tiles: workgroups are dealt to the L2
+// domains round-robin, and a domain keeps to few column tiles (the kernels undo this map).
+static int64_t grid_size(int64_t T, int64_t Q)
+{
+    if (Q >= kXcd) return (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
+    return (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
+}
+
+// The panels first (they are the long-running workgroups), then either one mixed launch (several
+// slab classes, none of which alone gives every CU a couple of workgroups) or one launch per slab
+// class present.
+int plan_launches(const vbr *v, int64_t N, Launch out[VBR_MAX_LAUNCHES])
+{
+    int n = 0;
+    const int64_t Qt = (N + kTileN - 1) / kTileN, Qp = (N + kPanelN - 1) / kPanelN;
+    if (!v->panels.empty())
+        out[n++] = Launch{VBR_LAUNCH_PANEL, 0, (int32_t)v->panels.size(), grid_size((int64_t)v->panels.size(), Qp)};
+    int classes = 0;
+    for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
+    const int64_t T_all = v->class_begin[4];
+    if (classes > 1 && T_all * Qt < 4096) {
+        out[n++] = Launch{VBR_LAUNCH_TILE_MIXED, 0, (int32_t)T_all, grid_size(T_all, Qt)};
+        return n;
+    }
+    for (int c = 0; c < 4; ++c) {
+        const int32_t T = v->class_begin[c + 1] - v->class_begin[c];
+        if (T > 0) out[n++] = Launch{VBR_LAUNCH_TILE_1 + c, v->class_begin[c], T, grid_size(T, Qt)};
+    }
+    return n;
+}
+
+}  // namespace vbrk
+
+extern "C" int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *kinds, int64_t *tiles, int64_t *workgroups)
+{
+    if (!v || !n_launches || N < 0) return VBR_EINVAL;
+    vbrk::Launch plan[VBR_MAX_LAUNCHES];
+    const int n = (N == 0 || v->n_rows == 0) ? 0 : vbrk::plan_launches(v, N, plan);
+    *n_launches = n;
+    for (int i = 0; i < n; ++i) {
+        if (kinds) kinds[i] = plan[i].kind;
+        if (tiles) tiles[i] = plan[i].n_tiles;
+        if (workgroups) workgroups[i] = plan[i].grid;
+    }
+    return VBR_OK;
+}
 
 extern "C" int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems)
 {

@@ -14,6 +14,9 @@ constexpr int kSlabRows = 16;       // rows of one MFMA slab
 constexpr int kStepK = 32;          // B rows consumed per K-step (one 16x16x32 MFMA deep)
 constexpr int kMaxSlabs = 8;        // slabs per workgroup tile (128 rows)
 constexpr int kFragElems = kSlabRows * kStepK;   // 512 16-bit values = 1 KiB per (slab, K-step)
+constexpr int kTileN = 256;         // C columns per workgroup of the tile kernel
+constexpr int kPanelN = 128;        // C columns per workgroup of the panel kernel
+constexpr int kXcd = 8;             // L2 domains; workgroup i runs on domain i % 8
 
 // One workgroup tile: up to kMaxSlabs slabs of ONE row group, walked over the group's K-steps.
 struct TileDesc {

@@ -18,12 +18,10 @@ void set_last_hip_error(int code) { g_last_hip_error = code; }
 namespace {
 
 constexpr int kThreads = 256;          // 4 waves
-constexpr int kTileN = 256;            // C columns per workgroup
 constexpr int kWaveN = 64;             // C columns per wave: 4 MFMA tiles of 16
 constexpr int kRowBytes = kTileN * 2;  // one staged B row in LDS: 512 bytes, no padding
 constexpr int kPanelBytes = kStepK * kRowBytes;   // 16 KiB of B per K-step
 constexpr int kFragBytes = kFragElems * 2;        // 1 KiB per A fragment
-constexpr int kXcd = 8;                // L2 domains; workgroup i runs on domain i % 8
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
@@ -566,37 +564,6 @@ constexpr int kStagesTall = 3;  // the same for tiles of 5 to 8 slabs (80 KiB of
                                 // to 14 % (K = 8 192) faster than 2 on dense matrices; slower than 2 for every lower class
 constexpr int kADistance = 3;   // K-steps the A fragments are requested ahead
 
-// Workgroups of a launch over T row tiles and Q column tiles (see map_workgroup).
-inline int64_t grid_size(int64_t T, int64_t Q)
-{
-    if (Q >= kXcd) return (int64_t)kXcd * ((Q + kXcd - 1) / kXcd) * T;
-    return (int64_t)kXcd * ((T + (kXcd / Q) - 1) / (kXcd / Q));
-}
-
-// The launches one vbr_spmm call issues for dense width N, in issue order: the panels first (they
-// are the long-running workgroups), then either one mixed launch (several slab classes, none of
-// which alone gives every CU a couple of workgroups) or one launch per slab class present.
-struct Launch { int32_t kind; int32_t first_tile, n_tiles; int64_t grid; };
-int plan_launches(const vbr *v, int64_t N, Launch out[VBR_MAX_LAUNCHES])
-{
-    int n = 0;
-    const int64_t Qt = (N + kTileN - 1) / kTileN, Qp = (N + 127) / 128;
-    if (!v->panels.empty())
-        out[n++] = Launch{VBR_LAUNCH_PANEL, 0, (int32_t)v->panels.size(), grid_size((int64_t)v->panels.size(), Qp)};
-    int classes = 0;
-    for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
-    const int64_t T_all = v->class_begin[4];
-    if (classes > 1 && T_all * Qt < 4096) {
-        out[n++] = Launch{VBR_LAUNCH_TILE_MIXED, 0, (int32_t)T_all, grid_size(T_all, Qt)};
-        return n;
-    }
-    for (int c = 0; c < 4; ++c) {
-        const int32_t T = v->class_begin[c + 1] - v->class_begin[c];
-        if (T > 0) out[n++] = Launch{VBR_LAUNCH_TILE_1 + c, v->class_begin[c], T, grid_size(T, Qt)};
-    }
-    return n;
-}
-
 template <int DT>
 int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStream_t stream)
 {
@@ -640,20 +607,6 @@ int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStrea
 }  // namespace vbrk
 
 extern "C" int vbr_last_hip_error(void) { return vbrk::g_last_hip_error; }
-
-extern "C" int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *kinds, int64_t *tiles, int64_t *workgroups)
-{
-    if (!v || !n_launches || N < 0) return VBR_EINVAL;
-    vbrk::Launch plan[VBR_MAX_LAUNCHES];
-    const int n = (N == 0 || v->n_rows == 0) ? 0 : vbrk::plan_launches(v, N, plan);
-    *n_launches = n;
-    for (int i = 0; i < n; ++i) {
-        if (kinds) kinds[i] = plan[i].kind;
-        if (tiles) tiles[i] = plan[i].n_tiles;
-        if (workgroups) workgroups[i] = plan[i].grid;
-    }
-    return VBR_OK;
-}
 
 extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
 {

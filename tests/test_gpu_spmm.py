@@ -17,7 +17,9 @@ TOL = 1e-4
 
 def gpu_spmm(csr, perm, rg, col_block, b_bits, ldb_pad=0, ldc_pad=0):
     import torch
-    v = binding.vbr_build(csr, perm, rg, col_block).upload("cuda:0")
+    v = binding.vbr_build(csr, perm, rg, col_block)
+    v.audit()                       # bounds of everything the kernels index, before anything is launched
+    v.upload("cuda:0")
     k, n = b_bits.shape
     if ldb_pad:
         full = np.zeros((k, n + ldb_pad), dtype=np.uint16)
@@ -415,3 +417,43 @@ def test_workloads_full_size_every_element(name):
         # rows without entries are exactly zero
         assert np.all(c[empty] == 0.0)
         del c, v
+
+
+# --------------------------------------------------------------------------- the comparison experiments, reduced
+CURVE_TAUS = [0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0]
+
+
+def blocked_and_csr_against_oracle(a, col_block, tau, b_bits, what):
+    import torch
+    perm, rg = blocking_bit_exact(a, col_block, tau)
+    c, v = gpu_spmm(a, perm, rg, col_block, b_bits)
+    index_bit_exact(v, a, perm, rg, col_block)
+    c_ref, s = oracle.spmm(a, b_bits)
+    check_c(c, c_ref, s, what + " blocked")
+    b = torch_io.bits_to_device(b_bits, a["dtype"])
+    c2 = binding.CsrDev(a).upload("cuda:0").spmm(b)
+    torch.cuda.synchronize()
+    check_c(c2.cpu().numpy().astype(np.float64), c_ref, s, what + " csr")
+
+
+@pytest.mark.parametrize("theta,rho", [(0.1, 0.05), (0.3, 0.5), (0.02, 0.2)])
+def test_landscape_point_at_the_selected_threshold(theta, rho):
+    # one point of the synthetic landscape A(Delta, theta, rho) at reduced size: the threshold the
+    # selection rule picks (same as the oracle's), then both kernels against the oracle
+    rng = np.random.default_rng(int(theta * 1000 + rho * 100))
+    a = synth.landscape(rng, 1024, 32, theta, rho)
+    b_bits = synth.dense_rhs(rng, 1024, 264, "f16")
+    sel = binding.sa1_blocking_curve(a, 32, CURVE_TAUS, 32)["selected"]
+    assert sel == oracle.blocking_curve(a, 32, CURVE_TAUS, 32)["selected"]
+    blocked_and_csr_against_oracle(a, 32, CURVE_TAUS[sel], b_bits, "landscape theta=%g rho=%g" % (theta, rho))
+
+
+@pytest.mark.parametrize("degree,col_block", [(8, 64), (8, 256), (128, 64), (128, 256), (32, 128)])
+def test_graph_grid_points_reduced(degree, col_block):
+    # corners and centre of the graph grid (edges per node x column-block width) at 2^11 nodes
+    w = synth.workload("rmat", scale=0.125, rmat_degree=degree, rmat_col_block=col_block)
+    a = w["A"]
+    sel = binding.sa1_blocking_curve(a, col_block, CURVE_TAUS, col_block)["selected"]
+    assert sel == oracle.blocking_curve(a, col_block, CURVE_TAUS, col_block)["selected"]
+    for tau in {CURVE_TAUS[sel], 0.4}:
+        blocked_and_csr_against_oracle(a, col_block, tau, w["B"], "rmat degree=%d cb=%d tau=%g" % (degree, col_block, tau))

@@ -39,6 +39,7 @@ def assert_same_blocking(csr, col_block, tau):
 def assert_same_index(csr, perm, rg, col_block, check_values=True):
     bp0, bc0, bo0 = oracle.vbr_index(csr, perm, rg, col_block)
     v = binding.vbr_build(csr, perm, rg, col_block)
+    v.audit()                       # every index the kernels use lies inside what it indexes
     ix = v.index()
     assert np.array_equal(ix["perm"], perm) and np.array_equal(ix["row_groups"], rg)
     assert np.array_equal(ix["blk_ptr"], bp0)

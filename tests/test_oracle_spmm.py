@@ -88,3 +88,20 @@ def test_product_does_not_depend_on_the_row_order_of_the_input():
     order = rng.permutation(30)
     c_p, _ = oracle.spmm(synth.permute_rows(csr, order), b)
     assert np.array_equal(c_p, c[order])
+
+
+def test_landscape_generator_draws_what_section_4_1_states():
+    # input generator only (no method arithmetic): theta of ALL blocks flagged, rho of the entries
+    # of each flagged block kept, rows scrambled
+    from paper_2202_05868_amd import synth
+    rng = np.random.default_rng(5)
+    n, delta, theta, rho = 512, 32, 0.2, 0.1
+    a = synth.landscape(rng, n, delta, theta, rho, scramble=False)
+    g = n // delta
+    rows = np.repeat(np.arange(n), np.diff(a["row_ptr"]))
+    blk = (rows // delta) * g + a["col_idx"] // delta
+    ids, counts = np.unique(blk, return_counts=True)
+    assert ids.size == round(theta * g * g)
+    assert np.all(counts == round(rho * delta * delta))
+    b = synth.landscape(np.random.default_rng(5), n, delta, theta, rho)      # same draw, rows scrambled
+    assert b["nnz"] == a["nnz"] and sorted(np.diff(b["row_ptr"]).tolist()) == sorted(np.diff(a["row_ptr"]).tolist())
