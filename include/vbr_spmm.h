@@ -13,7 +13,7 @@
  *                 only the nonzero blocks, zero-filled (section 2, section 3.1 last paragraph).
  *   vbr_spmm      C = A.B, every stored block multiplied as a small dense product on the
  *                 matrix units (section 4.4.1), in one launch per kernel class the matrix
- *                 needs (at most five: see vbr_spmm below).
+ *                 needs (at most six: see vbr_get_launches below).
  *
  * sa1_reorder and vbr_build are deterministic integer host code.  vbr_spmm runs on the GPU.
  * All pointers are HOST pointers unless the name ends in _dev.  Nothing is retained from the
@@ -132,8 +132,11 @@ int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
  * B and C must not overlap each other or the uploaded buffer.
  * Non-finite values: the zero fill-in of a stored block is multiplied like any other value, so a
  * NaN or Inf in B row k reaches every C row whose group stores the column block of k (the
- * format's semantics), and, for groups lower than 16 rows, also the rows of the other low groups
- * that share their 16-row slab.  B rows of column blocks that no group stores are never read.
+ * format's semantics).  For groups lower than 16 rows, which are multiplied in slabs of 16 rows
+ * cut across group boundaries, it reaches the rows of the slabs that hold such a group when the
+ * slabs share whole column blocks (panels), and only the rows of the slabs one of whose rows has
+ * an entry in column k itself when they gather single columns.  B rows of column blocks that no
+ * group stores are never read.
  */
 int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,
              int64_t N, void *hip_stream);
@@ -141,16 +144,19 @@ int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64
 /*
  * The kernel launches one vbr_spmm call with dense width N issues, in issue order (for reporting;
  * vbr_spmm itself launches from the same plan).  Rows of groups lower than 16 rows are multiplied
- * by the panel kernel, the other groups by the tile kernel, either in one launch per class of tile
+ * 128 at a time, by the panel kernel (their slabs of 16 rows share the B rows of the union of their
+ * column blocks) or by the tile kernel on column-gathered slabs (every slab loads exactly the B rows
+ * of the columns its rows touch), whichever packing needs fewer loads; the other groups by the tile
+ * kernel, either in one launch per class of tile
  * height that occurs (1, 2, 3-4, 5-8 slabs of 16 rows) or, for small matrices, in one launch that
  * mixes the classes: between 0 and VBR_MAX_LAUNCHES launches.  kinds / tiles / workgroups (each
  * room for VBR_MAX_LAUNCHES entries, any may be NULL) receive the kernel, the number of row tiles
  * or panels, and the grid size of each launch.
  */
-enum { VBR_MAX_LAUNCHES = 5 };
+enum { VBR_MAX_LAUNCHES = 6 };
 enum {
     VBR_LAUNCH_PANEL = 0, VBR_LAUNCH_TILE_1 = 1, VBR_LAUNCH_TILE_2 = 2, VBR_LAUNCH_TILE_4 = 3,
-    VBR_LAUNCH_TILE_8 = 4, VBR_LAUNCH_TILE_MIXED = 5
+    VBR_LAUNCH_TILE_8 = 4, VBR_LAUNCH_TILE_MIXED = 5, VBR_LAUNCH_GATHER = 6
 };
 int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *kinds, int64_t *tiles,
                      int64_t *workgroups);

@@ -192,7 +192,8 @@ class Vbr:
         return dict(n_tiles=a.value, n_ksteps=b.value, packed_elems=c.value)
 
     LAUNCH_KINDS = ("vbr_spmm_panel_kernel", "vbr_spmm_kernel<1 slab>", "vbr_spmm_kernel<2 slabs>",
-                    "vbr_spmm_kernel<4 slabs>", "vbr_spmm_kernel<8 slabs>", "vbr_spmm_mixed_kernel")
+                    "vbr_spmm_kernel<4 slabs>", "vbr_spmm_kernel<8 slabs>", "vbr_spmm_mixed_kernel",
+                    "vbr_spmm_kernel<1 slab, column-gathered>")
 
     def launches(self, n: int) -> list:
         """The kernel launches one ``spmm`` with dense width ``n`` issues, from the library's plan."""

@@ -26,6 +26,10 @@ inline int slab_class(int n_slabs)   // kernels exist for 1, 2, 4 and 8 slabs
 constexpr int kPanelSlabs = 8;
 constexpr int64_t kPanelMinRows = 4096;
 inline bool use_panels(int lg_gran, int64_t short_rows) { return lg_gran >= 3 && short_rows >= kPanelMinRows; }
+// Load instructions per K-step and 256 columns of C: a panel brings 32 B rows x 128 columns (8 loads)
+// and up to 8 fragments (8 loads) per 128 columns; a one-slab tile 32 B rows x 256 columns (16 loads)
+// and one fragment.  The direct-to-LDS load instruction is the unit of cost of both kernels.
+constexpr int64_t kPanelStepCost = 32, kTileStepCost = 17;
 
 int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups, int32_t G,
                int32_t col_block, vbr *v)
@@ -91,7 +95,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         v->ks_ptr[g + 1] = v->ks_ptr[g];
         v->group_first_tile[g + 1] = v->group_first_tile[g];
 
-        if (panels_on && h < kSlabRows) {           // short group: its rows join the panel region
+        if (h < kSlabRows) {                        // low group: its rows join the low rows
             v->group_prow[g] = (int32_t)v->prow.size();
             for (int64_t q = r0; q < r1; ++q) v->prow.push_back(perm[q]);
             continue;
@@ -127,8 +131,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         }
     }
 
-    // pass 2: panels.  Slabs are cut from the short rows in order; a panel walks the union of the
-    // column blocks of the groups its rows belong to.
+    // pass 2: the low rows, in chunks of 8 slabs.
     const int64_t n_prows = (int64_t)v->prow.size();
     std::vector<int32_t> prow_group((size_t)n_prows);
     for (int32_t g = 0; g < G; ++g)
@@ -138,12 +141,19 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     v->panel_slabs = n_prows > 0 ? R : 0;
     const int max_frags = kPanelMaxFrags;
     const int64_t panel_rows = (int64_t)R * kSlabRows;
-    const int64_t n_panels = (n_prows + panel_rows - 1) / panel_rows;
+    const int64_t n_panels = (n_prows + panel_rows - 1) / panel_rows;       // chunks
     v->p_union_ptr.assign(1, 0);
     std::vector<uint32_t> blk_mask;            // per union block: slabs that store it
     std::vector<int64_t> frag_of;              // [logical step][slab] -> fragment ordinal in the panel, -1
-    std::vector<int64_t> fill_dst, fill_src;   // panel values: position in vals <- position in csr->vals
-    for (int64_t pn = 0; pn < n_panels; ++pn) {
+    std::vector<int64_t> fill_dst, fill_src;   // low-row values: position in vals <- position in csr->vals
+    std::vector<int32_t> pos_of_col((size_t)std::max<int64_t>(csr->n_cols, 1), -1);
+    std::vector<int32_t> cols;
+    v->chunk_gather.assign((size_t)n_panels, 0);
+    v->chunk_index.assign((size_t)n_panels, 0);
+    int64_t g_ks = 0;                          // K-steps of the gathered tiles so far
+
+    auto emit_panel = [&](int64_t pn) -> int {
+        v->chunk_index[pn] = (int32_t)v->panels.size();
         const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
         // union of blocks, and per block the slabs that hold it
         blocks.clear();
@@ -221,6 +231,80 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         a_units += n_frags * (kFragElems / 8);
         for (int64_t u = 0; u < nu; ++u) pos_of_block[blocks[u]] = -1;
         v->panels.push_back(pd);
+        return VBR_OK;
+    };
+
+    // the slabs of a chunk as column-gathered tiles: K of a slab = the ascending list of the columns
+    // its rows touch, cut into K-steps of 32
+    auto emit_gather = [&](int64_t pn) -> int {
+        const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
+        v->chunk_gather[pn] = 1;
+        v->chunk_index[pn] = (int32_t)v->gtiles.size();
+        for (int64_t s0 = i0; s0 < i1; s0 += kSlabRows) {
+            const int64_t s1 = std::min(i1, s0 + kSlabRows);
+            cols.clear();
+            for (int64_t i = s0; i < s1; ++i) {
+                const int64_t r = v->prow[i];
+                for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p)
+                    if (pos_of_col[csr->col_idx[p]] < 0) { pos_of_col[csr->col_idx[p]] = 0; cols.push_back(csr->col_idx[p]); }
+            }
+            std::sort(cols.begin(), cols.end());
+            for (size_t k = 0; k < cols.size(); ++k) pos_of_col[cols[k]] = (int32_t)k;
+            const int64_t n_ks = ((int64_t)cols.size() + kStepK - 1) / kStepK;
+            if (g_ks + n_ks > INT32_MAX / 64) return VBR_EINVAL;
+            TileDesc td;
+            td.ks_begin = (int32_t)g_ks;
+            td.n_ks = (int32_t)n_ks;
+            td.a_off = a_units;
+            td.row_begin = (int32_t)s0;
+            td.n_rows = (int32_t)(s1 - s0);
+            td.n_slabs = 1;
+            td.group = -1;
+            const int64_t stride = tile_kstep_stride(td.n_rows, 1);
+            for (int64_t i = s0; i < s1; ++i) {
+                const int64_t r = v->prow[i];
+                for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                    const int64_t k = pos_of_col[csr->col_idx[p]];
+                    fill_dst.push_back(a_units * 8 + (k / kStepK) * stride + frag_index((int)(i - s0), (int)(k % kStepK), td.n_rows));
+                    fill_src.push_back(p);
+                }
+            }
+            for (int64_t k = 0; k < n_ks * kStepK; ++k) v->gcol.push_back(k < (int64_t)cols.size() ? cols[k] : -1);
+            for (const int32_t c : cols) pos_of_col[c] = -1;
+            a_units += n_ks * stride / 8;
+            g_ks += n_ks;
+            v->gtiles.push_back(td);
+        }
+        return VBR_OK;
+    };
+
+    for (int64_t pn = 0; pn < n_panels; ++pn) {
+        const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
+        bool gather = !panels_on;
+        if (!gather) {
+            // loads of the two packings for this chunk (per 256 columns of C)
+            blocks.clear();
+            int64_t cost_gather = 0;
+            for (int64_t s0 = i0; s0 < i1; s0 += kSlabRows) {
+                cols.clear();
+                for (int64_t i = s0; i < std::min(i1, s0 + kSlabRows); ++i) {
+                    const int64_t r = v->prow[i];
+                    for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                        const int32_t c = csr->col_idx[p];
+                        if (pos_of_col[c] < 0) { pos_of_col[c] = 0; cols.push_back(c); }
+                        const int32_t j = c / col_block;
+                        if (pos_of_block[j] < 0) { pos_of_block[j] = 0; blocks.push_back(j); }
+                    }
+                }
+                for (const int32_t c : cols) pos_of_col[c] = -1;
+                cost_gather += (((int64_t)cols.size() + kStepK - 1) / kStepK) * kTileStepCost;
+            }
+            for (const int32_t j : blocks) pos_of_block[j] = -1;
+            const int64_t cost_panel = (((int64_t)blocks.size() * col_block + kStepK - 1) / kStepK) * kPanelStepCost;
+            gather = cost_gather < cost_panel;
+        }
+        const int rc = gather ? emit_gather(pn) : emit_panel(pn);
+        if (rc != VBR_OK) return rc;
     }
 
     // pass 3: the values.  One allocation: tiles' fragments, panels' fragments, and one fragment
@@ -274,12 +358,13 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     DeviceLayout &L = v->lay;
     L.zeros_off = 0;                   // 256 zero bytes the kernel reads for padding
     L.tiles_off = 256;
-    L.krow_off = align_up(L.tiles_off + NT * (int64_t)sizeof(TileDesc), 256);
+    L.krow_off = align_up(L.tiles_off + (NT + (int64_t)v->gtiles.size()) * (int64_t)sizeof(TileDesc), 256);
     L.perm_off = align_up(L.krow_off + (int64_t)v->krow.size() * 4, 256);
     L.panels_off = align_up(L.perm_off + M * 4, 256);
     L.pk_meta_off = align_up(L.panels_off + (int64_t)v->panels.size() * (int64_t)sizeof(PanelDesc), 256);
     L.prow_off = align_up(L.pk_meta_off + (int64_t)v->pk_meta.size() * 4, 256);
-    L.vals_off = align_up(L.prow_off + n_prows * 4, 256);
+    L.gcol_off = align_up(L.prow_off + n_prows * 4, 256);
+    L.vals_off = align_up(L.gcol_off + (int64_t)v->gcol.size() * 4, 256);
     L.total = std::max<int64_t>(256, align_up(L.vals_off + (int64_t)v->vals.size() * 2, 256));
     return VBR_OK;
 }
@@ -344,16 +429,34 @@ extern "C" int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst_)
     const int64_t cb = v->col_block;
     uint16_t *dst = static_cast<uint16_t *>(dst_);
     if (v->group_prow[g] >= 0) {
-        // short group: its rows sit in a panel (or two); find the fragments through the panel's union
+        // low group: its rows sit in one chunk of the low rows (or two), packed as a panel or as
+        // column-gathered tiles
         const int64_t h = v->row_groups[g + 1] - v->row_groups[g];
         const int R = v->panel_slabs;
         const int64_t panel_rows = (int64_t)R * kSlabRows;
         for (int64_t i = 0; i < h; ++i) {
             const int64_t pi = v->group_prow[g] + i;
             const int64_t pn = pi / panel_rows;
-            const PanelDesc &pd = v->panels[pn];
+            if (v->chunk_gather[pn]) {
+                // the slab's column list is ascending up to its padding: look every column of the block up
+                const TileDesc &td = v->gtiles[v->chunk_index[pn] + (pi - pn * panel_rows) / kSlabRows];
+                const int m = (int)(pi - td.row_begin);
+                const int32_t *cb0 = &v->gcol[(size_t)td.ks_begin * kStepK], *ce = cb0 + (size_t)td.n_ks * kStepK;
+                while (ce > cb0 && ce[-1] < 0) --ce;
+                const int64_t stride = tile_kstep_stride(td.n_rows, 1);
+                for (int64_t c = 0; c < cb; ++c) {
+                    const int32_t col = (int32_t)((int64_t)v->blk_col[blk] * cb + c);
+                    const int32_t *it = std::lower_bound(cb0, ce, col);
+                    if (it == ce || *it != col) { dst[i * cb + c] = 0; continue; }      // fill-in: not stored
+                    const int64_t k = it - cb0;
+                    dst[i * cb + c] = v->vals[(size_t)td.a_off * 8 + (size_t)((k / kStepK) * stride) + frag_index(m, (int)(k % kStepK), td.n_rows)];
+                }
+                continue;
+            }
+            const int64_t pidx = v->chunk_index[pn];
+            const PanelDesc &pd = v->panels[pidx];
             const int s = (int)((pi - pd.row_begin) / kSlabRows), m = (int)((pi - pd.row_begin) % kSlabRows);
-            const int32_t *ub = &v->p_union[v->p_union_ptr[pn]], *ue = &v->p_union[0] + v->p_union_ptr[pn + 1];
+            const int32_t *ub = &v->p_union[v->p_union_ptr[pidx]], *ue = &v->p_union[0] + v->p_union_ptr[pidx + 1];
             const int64_t u = std::lower_bound(ub, ue, v->blk_col[blk]) - ub;
             for (int64_t c = 0; c < cb; ++c) {
                 const int64_t k = u * cb + c;
@@ -444,18 +547,28 @@ extern "C" int vbr_audit(const vbr_t *v)
             if (v->pk_meta[((int64_t)pd.meta_begin + k) * rec] != 0) return VBR_EINVAL;      // look-ahead records carry no slab
         if (pd.a_off < 0 || pd.a_off * 8 + frags * kFragElems > n_vals - kFragElems) return VBR_EINVAL;
     }
+    if ((int64_t)v->gcol.size() % kStepK != 0) return VBR_EINVAL;
+    for (const int32_t c : v->gcol)
+        if (c < -1 || c >= K) return VBR_EINVAL;
+    for (const TileDesc &td : v->gtiles) {
+        if (td.n_rows < 1 || td.n_rows > kSlabRows || td.n_slabs != 1) return VBR_EINVAL;
+        if (td.row_begin < 0 || (int64_t)td.row_begin + td.n_rows > (int64_t)v->prow.size()) return VBR_EINVAL;
+        if (td.n_ks < 0 || td.ks_begin < 0 || ((int64_t)td.ks_begin + td.n_ks) * kStepK > (int64_t)v->gcol.size()) return VBR_EINVAL;
+        if (td.a_off < 0 || td.a_off * 8 + (int64_t)td.n_ks * tile_kstep_stride(td.n_rows, 1) > n_vals - kFragElems) return VBR_EINVAL;
+    }
     for (size_t i = v->vals.size() - kFragElems; i < v->vals.size(); ++i)
         if (v->vals[i] != 0) return VBR_EINVAL;                                               // the zero fragment
     const DeviceLayout &L = v->lay;
-    const int64_t ends[8] = {L.zeros_off + 256, L.tiles_off + (int64_t)v->tiles.size() * (int64_t)sizeof(TileDesc),
-                             L.krow_off + (int64_t)v->krow.size() * 4, L.perm_off + M * 4,
-                             L.panels_off + (int64_t)v->panels.size() * (int64_t)sizeof(PanelDesc),
-                             L.pk_meta_off + (int64_t)v->pk_meta.size() * 4, L.prow_off + (int64_t)v->prow.size() * 4,
-                             L.vals_off + n_vals * 2};
-    const int64_t begins[8] = {L.zeros_off, L.tiles_off, L.krow_off, L.perm_off, L.panels_off, L.pk_meta_off, L.prow_off, L.vals_off};
-    for (int i = 0; i < 8; ++i) {
+    const int64_t ends[9] = {L.zeros_off + 256, L.tiles_off + (int64_t)(v->tiles.size() + v->gtiles.size()) * (int64_t)sizeof(TileDesc),
+                              L.krow_off + (int64_t)v->krow.size() * 4, L.perm_off + M * 4,
+                              L.panels_off + (int64_t)v->panels.size() * (int64_t)sizeof(PanelDesc),
+                              L.pk_meta_off + (int64_t)v->pk_meta.size() * 4, L.prow_off + (int64_t)v->prow.size() * 4,
+                              L.gcol_off + (int64_t)v->gcol.size() * 4, L.vals_off + n_vals * 2};
+    const int64_t begins[9] = {L.zeros_off, L.tiles_off, L.krow_off, L.perm_off, L.panels_off, L.pk_meta_off, L.prow_off,
+                               L.gcol_off, L.vals_off};
+    for (int i = 0; i < 9; ++i) {
         if (begins[i] % 256 != 0 || ends[i] > L.total) return VBR_EINVAL;
-        if (i + 1 < 8 && ends[i] > begins[i + 1]) return VBR_EINVAL;                          // sections in this order, disjoint
+        if (i + 1 < 9 && ends[i] > begins[i + 1]) return VBR_EINVAL;                         // sections in this order, disjoint
     }
     return VBR_OK;
 }
@@ -481,13 +594,16 @@ int plan_launches(const vbr *v, int64_t N, Launch out[VBR_MAX_LAUNCHES])
     const int64_t Qt = (N + kTileN - 1) / kTileN, Qp = (N + kPanelN - 1) / kPanelN;
     if (!v->panels.empty())
         out[n++] = Launch{VBR_LAUNCH_PANEL, 0, (int32_t)v->panels.size(), grid_size((int64_t)v->panels.size(), Qp)};
-    int classes = 0;
+    // the column-gathered slabs follow the tiles of the four classes in the device's tile array
+    const int64_t T_low = (int64_t)v->gtiles.size();
+    int classes = T_low > 0 ? 1 : 0;
     for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
-    const int64_t T_all = v->class_begin[4];
+    const int64_t T_all = v->class_begin[4] + T_low;
     if (classes > 1 && T_all * Qt < 4096) {
         out[n++] = Launch{VBR_LAUNCH_TILE_MIXED, 0, (int32_t)T_all, grid_size(T_all, Qt)};
         return n;
     }
+    if (T_low > 0) out[n++] = Launch{VBR_LAUNCH_GATHER, v->class_begin[4], (int32_t)T_low, grid_size(T_low, Qt)};
     for (int c = 0; c < 4; ++c) {
         const int32_t T = v->class_begin[c + 1] - v->class_begin[c];
         if (T > 0) out[n++] = Launch{VBR_LAUNCH_TILE_1 + c, v->class_begin[c], T, grid_size(T, Qt)};
@@ -514,8 +630,8 @@ extern "C" int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, 
 extern "C" int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems)
 {
     if (!v) return VBR_EINVAL;
-    if (n_tiles) *n_tiles = (int64_t)v->tiles.size() + (int64_t)v->panels.size();
-    if (n_ksteps) *n_ksteps = v->ks_ptr.back() + (int64_t)v->pk_mask.size();
+    if (n_tiles) *n_tiles = (int64_t)v->tiles.size() + (int64_t)v->panels.size() + (int64_t)v->gtiles.size();
+    if (n_ksteps) *n_ksteps = v->ks_ptr.back() + (int64_t)v->pk_mask.size() + (int64_t)v->gcol.size() / vbrk::kStepK;
     if (packed_elems) *packed_elems = (int64_t)v->vals.size();
     return VBR_OK;
 }

@@ -74,6 +74,7 @@ constexpr int kPanelMetaPad = 12;    // records appended to a panel's K-step str
 struct DeviceLayout {
     int64_t zeros_off = 0, tiles_off = 0, krow_off = 0, perm_off = 0, vals_off = 0, total = 0;
     int64_t panels_off = 0, pk_meta_off = 0, prow_off = 0;
+    int64_t gcol_off = 0;      // (the column-gathered tiles follow the other tiles in the tiles section)
 };
 
 }  // namespace vbrk
@@ -95,10 +96,17 @@ struct vbr {
     std::vector<int64_t> group_first_tile;      // [n_groups+1] tiles of a group in creation order (for unpack)
     std::vector<int32_t> tile_of_group_order;   // creation order -> index in `tiles`
     std::vector<uint16_t> vals;          // packed fragments: tiles first, then panels, then 1 KiB of zeros
-    // panels: rows of groups of height < 16 (when the block width is a multiple of 8)
-    int32_t panel_slabs = 0;             // slabs per panel; 0 = the matrix has no panels
-    std::vector<int32_t> prow;           // original row of every panel-region row, in permuted order
-    std::vector<int32_t> group_prow;     // [n_groups] first panel-region row of a short group, -1 for tall groups
+    // Rows of groups of height < 16 ("low rows") are collected in permuted order (prow) and cut into
+    // chunks of 128 rows = 8 slabs.  A chunk is packed either as ONE PANEL (its slabs share the B rows
+    // of the union of their column blocks) or as 8 COLUMN-GATHERED TILES (each slab gathers exactly
+    // the B rows of the columns its own rows touch), whichever needs fewer loads.
+    int32_t panel_slabs = 0;             // slabs per chunk (8); 0 = the matrix has no low rows
+    std::vector<int32_t> prow;           // original row of every low row, in permuted order
+    std::vector<int32_t> group_prow;     // [n_groups] first low-row position of a low group, -1 for the others
+    std::vector<uint8_t> chunk_gather;   // [n_chunks] 1 = packed as column-gathered tiles, 0 = as a panel
+    std::vector<int32_t> chunk_index;    // [n_chunks] index of its panel in `panels`, or of its first tile in `gtiles`
+    std::vector<vbrk::TileDesc> gtiles;   // column-gathered tiles: one slab each, row_begin = position in prow, group = -1
+    std::vector<int32_t> gcol;           // per K-step of a gathered tile 32 columns of A (= rows of B), ascending, -1 = padding
     std::vector<vbrk::PanelDesc> panels;
     std::vector<int32_t> pk_row;         // host only: first B row of each granule of each physical K-step, -1 = padding
     std::vector<uint32_t> pk_mask;       // host only: slabs present in each physical K-step

@@ -34,9 +34,11 @@ typedef __attribute__((address_space(3))) unsigned char *lds_u8_ptr;
 typedef __attribute__((address_space(4))) const int32_t *const_i32_ptr;
 
 struct Params {
-    const TileDesc *tiles;    // tiles of this launch's slab class
+    const TileDesc *tiles;    // tiles of this launch: one slab class, all of them, or the column-gathered ones
     const int32_t *krow;
     const int32_t *perm;
+    const int32_t *gcol;      // column-gathered tiles: their column lists ...
+    const int32_t *prow;      // ... and the list of the low rows their row positions refer to
     const uint16_t *vals;
     const uint16_t *zeros;    // 256 zero bytes: source of padding rows, padding lanes and columns >= N
     const uint16_t *B;
@@ -109,10 +111,14 @@ __device__ __forceinline__ bool map_workgroup(int T, int Q, int &tile, int &ntil
 template <int S, int NS, int DA>
 constexpr int tile_lds_bytes() { return NS * kPanelBytes + (DA + 1) * S * kFragBytes; }
 
-template <int DT, int S, int NS, int DA>
+// GATHER: the tile is a slab of rows of low row groups whose K dimension is the list of the single
+// COLUMNS its rows touch (one gather entry per B row, krow = that list) instead of whole column
+// blocks: the fill-in columns of the blocks, which hold nothing but zeros, are never loaded.
+template <int DT, int S, int NS, int DA, bool GATHER = false>
 __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, const int ntile, unsigned char *smem)
 {
     static_assert(NS >= 2 && DA >= NS - 1, "A must be requested before the B panel of its K-step");
+    static_assert(!GATHER || S == 1, "column-gathered tiles are single slabs");
     constexpr int NA = S >= 4 ? S / 4 : 1;      // A loads per wave per K-step
     constexpr int NAS = DA + 1;
     constexpr int kAStage = S * kFragBytes;
@@ -197,15 +203,34 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         // K-step whose B loads are issued next (rb0) and the one after (rb1): scalar loads, issued
         // two iterations ahead of their use.  Narrower blocks look their rows up per lane at issue
         // time instead, with an ordinary load the compiler waits for (slow, but rare and simple).
-        int rb0 = -1, rb1 = -1;
-        auto load_rows = [&](int ks) -> int {
+        // Column-gathered tiles: the 8 B rows of the wave, one list entry each, as 8 scalars.
+        struct Rows { int r[GATHER ? 8 : 1]; };
+        Rows rb0, rb1;
+        rb0.r[0] = rb1.r[0] = -1;
+        auto load_rows = [&](int ks) -> Rows {
             const int kc = ks < n_ks ? ks : n_ks - 1;      // past the end: reload the last K-step (never computed)
-            return lg >= 3 ? krow[(kc * kStepK + 8 * wave) >> lg] : -1;
+            Rows out;
+            if constexpr (GATHER) {
+                const const_i32_ptr src = (const_i32_ptr)p.gcol + ((int64_t)td.ks_begin + kc) * kStepK + 8 * wave;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) out.r[j] = src[j];
+            } else {
+                out.r[0] = lg >= 3 ? krow[(kc * kStepK + 8 * wave) >> lg] : -1;
+            }
+            return out;
         };
         auto issue_b = [&](int ks, int slot) {
             const uint32_t sb = smem_base + slot * kPanelBytes + 8 * wave * kRowBytes;
-            if (tile_fast && rb0 >= 0) {
-                const char *rowptr = Btile + (uint64_t)(uint32_t)rb0 * ldb_bytes;          // scalar, 64-bit
+            if constexpr (GATHER) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = half ? rb0.r[2 * i + 1] : rb0.r[2 * i];
+                    // chunks at or beyond column N re-read the tile's last existing chunk, as on the fast path
+                    const char *src = e >= 0 ? Btile + (uint64_t)(uint32_t)e * ldb_bytes + (b_col_ok[i] ? b_col[i] : (uint32_t)last_chunk * 16) : zeros;
+                    dma16(src, sb + 2 * i * kRowBytes);
+                }
+            } else if (tile_fast && rb0.r[0] >= 0) {
+                const char *rowptr = Btile + (uint64_t)(uint32_t)rb0.r[0] * ldb_bytes;          // scalar, 64-bit
 #pragma unroll
                 for (int i = 0; i < 4; ++i) dma16_base(b_lane[i], rowptr, sb + 2 * i * kRowBytes);
             } else {         // narrow blocks, padding rows or column tail: zeros come from the zero page
@@ -213,7 +238,7 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int r = 8 * wave + 2 * i + half;
-                    const int e = lg >= 3 ? rb0 : p.krow[(int64_t)td.ks_begin * (kStepK >> lg) + ((kc * kStepK + r) >> lg)];
+                    const int e = lg >= 3 ? rb0.r[0] : p.krow[(int64_t)td.ks_begin * (kStepK >> lg) + ((kc * kStepK + r) >> lg)];
                     const char *src = (e >= 0 && b_col_ok[i]) ? Btile + (int64_t)(e + (r & gmask)) * ldb_bytes + b_col[i] : zeros;
                     dma16(src, sb + 2 * i * kRowBytes);
                 }
@@ -299,7 +324,7 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         for (int ks = 0; ks < n_ks; ++ks) {
             wait_stage(ks);                        // this wave's loads of K-step ks have landed
             __builtin_amdgcn_s_barrier();          // ... and everybody else's; the slots of K-step ks-1 are free
-            asm volatile("" ::"s"(rb0));           // the scalar row lookup is waited for here, not behind the LDS reads
+            asm volatile("" ::"s"(rb0.r[0]));      // the scalar row lookup is waited for here, not behind the LDS reads
             read_frags(bslot, aslot);
             // the load path is what bounds the kernel: a wave that is about to issue its loads goes
             // ahead of the waves that are multiplying (measured: 3-4 % on the 16-row workload)
@@ -321,7 +346,7 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
     for (int s = 0; s < S; ++s) {
         const int rr = s * kSlabRows + s16;
         if (rr < td.n_rows) {
-            const int64_t orig = p.perm[td.row_begin + rr];
+            const int64_t orig = (GATHER ? p.prow : p.perm)[td.row_begin + rr];
             float *crow = p.C + orig * p.ldc;
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
@@ -339,13 +364,13 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
 // Measured on the 16-row workload: two ring slots and four resident workgroups per CU (36 KiB of
 // LDS each) beat deeper rings with fewer workgroups; the gather is bound by how many independent
 // instruction streams feed the texture-address unit, not by the depth of any one of them.
-template <int DT, int S, int NS, int DA>
+template <int DT, int S, int NS, int DA, bool GATHER = false>
 __global__ void __launch_bounds__(kThreads) vbr_spmm_kernel(const Params p)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[tile_lds_bytes<S, NS, DA>()];
     int tile, ntile;
     if (!map_workgroup(p.n_tiles, p.n_ntiles, tile, ntile)) return;
-    tile_body<DT, S, NS, DA>(p, p.tiles[tile], ntile, smem);
+    tile_body<DT, S, NS, DA, GATHER>(p, p.tiles[tile], ntile, smem);
 }
 
 // All slab classes in one launch, for matrices whose classes are each too small to fill the chip:
@@ -357,7 +382,8 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_mixed_kernel(const Params p
     int tile, ntile;
     if (!map_workgroup(p.n_tiles, p.n_ntiles, tile, ntile)) return;
     const TileDesc td = p.tiles[tile];
-    if (td.n_slabs <= 1) tile_body<DT, 1, NS, DA>(p, td, ntile, smem);
+    if (td.group < 0) tile_body<DT, 1, NS, DA, true>(p, td, ntile, smem);        // column-gathered slab
+    else if (td.n_slabs <= 1) tile_body<DT, 1, NS, DA>(p, td, ntile, smem);
     else if (td.n_slabs <= 2) tile_body<DT, 2, NS, DA>(p, td, ntile, smem);
     else if (td.n_slabs <= 4) tile_body<DT, 4, NS, DA>(p, td, ntile, smem);
     else tile_body<DT, 8, NS, DA>(p, td, ntile, smem);
@@ -584,6 +610,9 @@ int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStrea
         case VBR_LAUNCH_TILE_MIXED:
             hipLaunchKernelGGL((vbr_spmm_mixed_kernel<DT, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
             break;
+        case VBR_LAUNCH_GATHER:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance, true>), grid, dim3(kThreads), 0, stream, p);
+            break;
         case VBR_LAUNCH_TILE_1:
             hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
             break;
@@ -616,7 +645,9 @@ extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
     const vbrk::DeviceLayout &L = v->lay;
     struct Part { int64_t off; const void *src; size_t bytes; };
     static const unsigned char kZeros[256] = {0};
-    const Part parts[8] = {
+    const Part parts[10] = {
+        {L.tiles_off + (int64_t)(v->tiles.size() * sizeof(vbrk::TileDesc)), v->gtiles.data(), v->gtiles.size() * sizeof(vbrk::TileDesc)},
+        {L.gcol_off, v->gcol.data(), v->gcol.size() * 4},
         {L.panels_off, v->panels.data(), v->panels.size() * sizeof(vbrk::PanelDesc)},
         {L.pk_meta_off, v->pk_meta.data(), v->pk_meta.size() * 4},
         {L.prow_off, v->prow.data(), v->prow.size() * 4},
@@ -677,6 +708,8 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     pp.lg_gran = v->lg_gran;
     pp.n_panels = (int32_t)v->panels.size();
     pp.n_ntiles = (int32_t)((N + 127) / 128);
+    p.gcol = reinterpret_cast<const int32_t *>(d + v->lay.gcol_off);
+    p.prow = pp.prow;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return v->dtype == VBR_F16 ? vbrk::launch_all<VBR_F16>(v, p, pp, stream) : vbrk::launch_all<VBR_BF16>(v, p, pp, stream);
 }

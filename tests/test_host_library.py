@@ -294,11 +294,20 @@ def test_launch_plan_lists_what_a_call_issues():
     assert [p["kernel"] for p in plan] == ["vbr_spmm_kernel<1 slab>"] and plan[0]["tiles"] == 8
     assert plan[0]["workgroups"] == 8 * 16
     assert v.launches(0) == []
-    # groups of 16 and of 100 rows: two classes, few tiles -> one mixed launch
+    # groups of 16 and of 100 rows: two classes, few tiles -> one mixed launch, which also takes the
+    # column-gathered slab the 12 rows left over (a low group) form
     v = binding.vbr_build(csr, np.arange(128, dtype=np.int32), np.array([0, 16, 116, 128], dtype=np.int32), 16)
-    assert [p["kernel"] for p in v.launches(256)] == ["vbr_spmm_mixed_kernel"]
-    # thousands of short rows: panels first
-    big = random_csr(rng, 6000, 64, 0.05)
+    plan = v.launches(256)
+    assert [p["kernel"] for p in plan] == ["vbr_spmm_mixed_kernel"] and plan[0]["tiles"] == 3
+    # thousands of single-row groups over 4 column blocks, every row touching most of them: one
+    # panel per 128 rows shares the few B rows there are; the same number of rows with one entry
+    # each over many columns: column-gathered slabs, 16 rows each
+    big = random_csr(rng, 6000, 64, 0.2)
     v = binding.vbr_build(big, np.arange(6000, dtype=np.int32), np.arange(0, 6001, dtype=np.int32), 16)
     plan = v.launches(256)
-    assert plan[0]["kernel"] == "vbr_spmm_panel_kernel" and plan[0]["tiles"] == (6000 + 127) // 128
+    assert [p["kernel"] for p in plan] == ["vbr_spmm_panel_kernel"] and plan[0]["tiles"] == (6000 + 127) // 128
+    wide = csr_from_rows([[int(c)] for c in rng.integers(0, 16384, size=6000)], n_cols=16384)
+    v = binding.vbr_build(wide, np.arange(6000, dtype=np.int32), np.arange(0, 6001, dtype=np.int32), 16)
+    plan = v.launches(256)
+    assert [p["kernel"] for p in plan] == ["vbr_spmm_kernel<1 slab, column-gathered>"] and plan[0]["tiles"] == 6000 // 16
+    v.audit()
