@@ -64,6 +64,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     v->group_prow.assign((size_t)std::max<int32_t>(G, 1), -1);
     std::vector<int32_t> pos_of_block((size_t)std::max<int64_t>(KB, 1), -1);
     std::vector<int32_t> blocks;
+    std::vector<int32_t> low_groups;            // groups lower than a slab, in group order
     std::vector<TileDesc> tiles;
     int64_t a_units = 0;   // running size of the packed values, in units of 8 values
 
@@ -95,9 +96,8 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         v->ks_ptr[g + 1] = v->ks_ptr[g];
         v->group_first_tile[g + 1] = v->group_first_tile[g];
 
-        if (h < kSlabRows) {                        // low group: its rows join the low rows
-            v->group_prow[g] = (int32_t)v->prow.size();
-            for (int64_t q = r0; q < r1; ++q) v->prow.push_back(perm[q]);
+        if (h < kSlabRows) {                        // low group: its rows join the low rows (ordered below)
+            low_groups.push_back(g);
             continue;
         }
 
@@ -128,6 +128,67 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             a_units += n_ks * tile_kstep_stride(td.n_rows, td.n_slabs) / 8;
             row += td.n_rows;
             tiles.push_back(td);
+        }
+    }
+
+    // The order of the low groups in the low-row list is free (C is written through the row list).
+    // Slabs cut from a list in which groups with similar block patterns follow each other gather
+    // far fewer B rows, so the list is built cluster by cluster: the first group not yet placed
+    // leads a cluster and takes with it every later group whose block set has a Jaccard similarity
+    // of at least 1/4 with the LEADER'S set (no pattern update: this only orders the packing, the
+    // blocking is the caller's).  Candidates come from an index column block -> low groups.  When
+    // the first 512 leaders find next to nothing (unstructured matrices), the rest keeps its order.
+    {
+        const int64_t n_low = (int64_t)low_groups.size();
+        std::vector<int32_t> order;
+        order.reserve((size_t)n_low);
+        std::vector<int64_t> inv_ptr((size_t)KB + 1, 0);
+        for (const int32_t g : low_groups)
+            for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) inv_ptr[v->blk_col[b] + 1]++;
+        for (int64_t b = 0; b < KB; ++b) inv_ptr[b + 1] += inv_ptr[b];
+        std::vector<int32_t> inv((size_t)inv_ptr[KB]);
+        {
+            std::vector<int64_t> fill(inv_ptr.begin(), inv_ptr.end() - 1);
+            for (int64_t i = 0; i < n_low; ++i) {
+                const int32_t g = low_groups[i];
+                for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) inv[fill[v->blk_col[b]]++] = (int32_t)i;
+            }
+        }
+        std::vector<int64_t> first(inv_ptr.begin(), inv_ptr.end() - 1);
+        std::vector<uint8_t> placed((size_t)n_low, 0);
+        std::vector<int32_t> cnt((size_t)n_low, 0), hit;
+        int64_t leaders = 0, followers = 0;
+        bool clustering = true;
+        for (int64_t i = 0; i < n_low; ++i) {
+            if (placed[i]) continue;
+            placed[i] = 1;
+            order.push_back((int32_t)i);
+            if (!clustering) continue;
+            const int32_t g = low_groups[i];
+            const int64_t li = v->blk_ptr[g + 1] - v->blk_ptr[g];
+            hit.clear();
+            for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) {
+                const int32_t blk = v->blk_col[b];
+                int64_t &f = first[blk];
+                while (f < inv_ptr[blk + 1] && inv[f] <= i) ++f;
+                for (int64_t e = f; e < inv_ptr[blk + 1]; ++e) {
+                    const int32_t j = inv[e];
+                    if (!placed[j] && cnt[j]++ == 0) hit.push_back(j);
+                }
+            }
+            std::sort(hit.begin(), hit.end());
+            for (const int32_t j : hit) {
+                const int32_t gj = low_groups[j];
+                const int64_t I = cnt[j], U = li + (v->blk_ptr[gj + 1] - v->blk_ptr[gj]) - I;
+                cnt[j] = 0;
+                if (4 * I >= U) { placed[j] = 1; order.push_back(j); ++followers; }
+            }
+            if (++leaders == 512 && followers < 64) clustering = false;
+        }
+        for (const int32_t i : order) {
+            const int32_t g = low_groups[i];
+            v->group_prow[g] = (int32_t)v->prow.size();
+            for (int64_t q = row_groups[g]; q < row_groups[g + 1]; ++q) v->prow.push_back(perm[q]);
         }
     }
 
@@ -594,7 +655,12 @@ int plan_launches(const vbr *v, int64_t N, Launch out[VBR_MAX_LAUNCHES])
     const int64_t Qt = (N + kTileN - 1) / kTileN, Qp = (N + kPanelN - 1) / kPanelN;
     if (!v->panels.empty())
         out[n++] = Launch{VBR_LAUNCH_PANEL, 0, (int32_t)v->panels.size(), grid_size((int64_t)v->panels.size(), Qp)};
-    // the column-gathered slabs follow the tiles of the four classes in the device's tile array
+    // Five tile classes, contiguous in the device's tile array: 1, 2, 3-4, 5-8 slabs, then the
+    // column-gathered slabs.  Several classes that together do not give every CU a few workgroups
+    // share one launch of the mixed kernel; otherwise every class present gets a launch of its own
+    // kernel, the gathered slabs first.  (Mixing only the small classes of a large matrix was
+    // measured and lost: the mixed kernel holds the LDS of the tallest class, and the tall tiles of the
+    // graph workload, few but with long block lists, ran 20 % longer in it.)
     const int64_t T_low = (int64_t)v->gtiles.size();
     int classes = T_low > 0 ? 1 : 0;
     for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
