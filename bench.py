@@ -125,6 +125,7 @@ def main() -> int:
         else:
             res = (experiments.rmat_grid(degrees=(8, 64), col_blocks=(64,), log2_nodes=12, width=1024, progress=say)
                    if args.small else experiments.rmat_grid(progress=say))
+        say(experiments.landscape_table(res) if args.landscape else experiments.rmat_table(res))
         print(json.dumps(res))
         return 0
 

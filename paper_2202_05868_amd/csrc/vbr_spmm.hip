@@ -264,8 +264,10 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
                 for (int d = 1; d <= NS - 1; ++d) later_a += a_turn(ks - d + DA) ? 1 : 0;
                 if (later_a == 0) wait_vmcnt<(NS - 2) * 4>();
                 else if (later_a == 1) wait_vmcnt<(NS - 2) * 4 + 1>();
-                else wait_vmcnt<(NS - 2) * 4 + 2>();
-                static_assert(NS <= 3, "at most two later A loads are told apart");
+                else if (later_a == 2) wait_vmcnt<(NS - 2) * 4 + 2>();
+                else if (later_a == 3) wait_vmcnt<(NS - 2) * 4 + 3>();
+                else wait_vmcnt<(NS - 2) * 4 + 4>();
+                static_assert(NS <= 5, "at most four later A loads are told apart");
             }
         };
 
@@ -585,6 +587,10 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
     }
 }
 
+#ifndef VBR_GNS
+#define VBR_GNS 2
+#define VBR_GDA 3
+#endif
 constexpr int kStages = 2;      // LDS ring of B panels
 constexpr int kStagesTall = 3;  // the same for tiles of 5 to 8 slabs (80 KiB of LDS, two workgroups per CU): measured 3 % (K = 16 384)
                                 // to 14 % (K = 8 192) faster than 2 on dense matrices; slower than 2 for every lower class
@@ -611,7 +617,7 @@ int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStrea
             hipLaunchKernelGGL((vbr_spmm_mixed_kernel<DT, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
             break;
         case VBR_LAUNCH_GATHER:
-            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance, true>), grid, dim3(kThreads), 0, stream, p);
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, VBR_GNS, VBR_GDA, true>), grid, dim3(kThreads), 0, stream, p);
             break;
         case VBR_LAUNCH_TILE_1:
             hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);

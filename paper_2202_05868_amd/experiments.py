@@ -121,3 +121,45 @@ def rmat_grid(degrees=(8, 16, 32, 64, 128), col_blocks=(64, 128, 256), log2_node
                     runs[best]["N"][str(width)]["speedup"], runs[best]["fill_in"]))
     return {"experiment": "blocked multiply vs CSR multiply on RMAT graphs, section 4.4.3", "nodes": n, "N": width,
             "taus": TAUS, "points": points}
+
+
+def landscape_table(res: dict) -> str:
+    """The landscape result as a text table (what is kept under profiles/)."""
+    widths = [k for k in res["points"][0]["N"]]
+    out = ["# Blocked multiply (1-SA -> VBR -> vbr_spmm) against the CSR multiply (csr_spmm) over the synthetic landscape",
+           "# A(Delta=%d, theta, rho), %d x %d, rows scrambled, tau of the blocking whose average block height is nearest to Delta" % (
+               res["delta"], res["n"], res["n"]),
+           "# (paper: section 4.4.2, Table 2).  fp16 -> fp32.  x = csr_ms / vbr_ms per dense width N.",
+           "command: python bench.py --landscape",
+           "",
+           "%-6s %-5s %9s %4s %8s %7s %8s" % ("theta", "rho", "nnz", "tau", "height", "rho'", "fill-in") +
+           "".join(" | N=%-5s vbr ms  csr ms      x" % n for n in widths)]
+    for p in res["points"]:
+        line = "%-6g %-5g %9d %4g %8.1f %7.3f %8.2f" % (p["theta"], p["rho"], p["nnz"], p["tau"], p["avg_block_height"],
+                                                        p["rho_after"], p["fill_in"])
+        for n in widths:
+            x = p["N"][n]
+            line += " | %14.3f %7.3f %6.2f" % (x["vbr_ms"], x["csr_ms"], x["speedup"])
+        out.append(line)
+    out.append("")
+    out.append("largest |C_vbr - C_csr| over all points: %.3g" % max(x["max_abs_diff"] for p in res["points"] for x in p["N"].values()))
+    return "\n".join(out) + "\n"
+
+
+def rmat_table(res: dict) -> str:
+    n = str(res["N"])
+    out = ["# Blocked multiply against the CSR multiply on RMAT graphs (0.57, 0.19, 0.19, 0.05), %d nodes, rows scrambled," % res["nodes"],
+           "# dense width N = %s (paper: section 4.1 Table 2, section 4.4.3).  The paper states no threshold for this experiment:" % n,
+           "# 'rule' = the tau of {0.1 .. 1} whose average block height is nearest to the column-block width, 'fastest' = the tau",
+           "# of the sweep with the shortest blocked multiply.  fp16 -> fp32.  x = csr_ms / vbr_ms.",
+           "command: python bench.py --rmat-grid",
+           "",
+           "%-7s %9s %-6s | %-4s %8s %8s %8s %6s | %-4s %8s %8s %6s" % ("degree", "nnz", "Dw", "tau", "fill-in", "vbr ms", "csr ms", "x",
+                                                                          "tau", "fill-in", "vbr ms", "x")]
+    for p in res["points"]:
+        a, b = p["selected_by_height"], p["fastest"]
+        xa, xb = a["N"][n], b["N"][n]
+        out.append("%-7d %9d %-6d | %-4g %8.1f %8.3f %8.3f %6.2f | %-4g %8.1f %8.3f %6.2f" % (
+            p["avg_degree_drawn"], p["nnz"], p["col_block"], a["tau"], a["fill_in"], xa["vbr_ms"], xa["csr_ms"], xa["speedup"],
+            b["tau"], b["fill_in"], xb["vbr_ms"], xb["speedup"]))
+    return "\n".join(out) + "\n"

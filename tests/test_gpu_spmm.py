@@ -114,6 +114,38 @@ def test_short_groups_in_panels():
     check_c(c, c_ref, s, "tiles and panels mixed")
 
 
+def test_low_rows_packed_both_ways_in_one_matrix():
+    # 3072 single-row groups that all touch the same 6 column blocks (one shared panel per 128 rows
+    # needs fewest loads), then 3072 rows with two entries each anywhere in 16384 columns (slabs that
+    # gather their own columns do), then one tall group: three kernels in one call; the low groups
+    # are handed over in scrambled order, so the packing's own ordering of them is at work too
+    rng = np.random.default_rng(91)
+    n_cols, cb = 16384, 16
+    dense_cols = np.concatenate([np.arange(b * cb, (b + 1) * cb) for b in (3, 70, 200, 511, 800, 1023)])
+    rows = [sorted(rng.choice(dense_cols, size=40, replace=False).tolist()) for _ in range(3072)]
+    rows += [sorted(set(rng.integers(0, n_cols, size=2).tolist())) for _ in range(3072)]
+    rows += [sorted(rng.choice(n_cols, size=30, replace=False).tolist()) for _ in range(40)]
+    csr = csr_from_rows(rows, n_cols=n_cols, rng=rng)
+    m = len(rows)
+    low = rng.permutation(6144).astype(np.int32)
+    perm = np.concatenate([low, np.arange(6144, m, dtype=np.int32)])
+    rg = np.concatenate([np.arange(0, 6145), [m]]).astype(np.int32)
+    b = synth.dense_rhs(rng, n_cols, 264, "f16")
+    c, v = gpu_spmm(csr, perm, rg, cb, b, ldb_pad=8, ldc_pad=4)
+    plan = v.launches(264)
+    # some twenty panels, then one launch with the ~200 gathered slabs and the tile of the tall group
+    assert plan[0]["kernel"] == "vbr_spmm_panel_kernel" and plan[0]["tiles"] >= 16
+    assert len(plan) == 2 and plan[1]["kernel"] == "vbr_spmm_mixed_kernel" and plan[1]["tiles"] >= 150
+    index_bit_exact(v, csr, perm, rg, cb)
+    c_ref, s = oracle.spmm(csr, b)
+    check_c(c, c_ref, s, "panels and gathered slabs")
+    ix = v.index()
+    for blk in rng.choice(ix["n_blocks"], size=300, replace=False):
+        g = int(np.searchsorted(ix["blk_ptr"], blk, side="right") - 1)
+        assert np.array_equal(v.unpack_block(int(blk), int(rg[g + 1] - rg[g]), cb),
+                              oracle.block_bits(csr, perm, rg, g, int(ix["blk_col"][blk]), cb))
+
+
 @pytest.mark.parametrize("col_block,n_blocks,density,dtype,n", [(16, 12, 0.03, "f16", 136), (32, 40, 0.01, "bf16", 264),
                                                               (16, 200, 0.004, "f16", 128)])
 def test_short_groups_wider_blocks_and_padded_leading_dimensions(col_block, n_blocks, density, dtype, n):
