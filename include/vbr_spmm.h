@@ -164,6 +164,13 @@ int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *ki
 /* Number of workgroup tiles and K-steps of the schedule (for reporting). */
 int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_ksteps, int64_t *packed_elems);
 
+/*
+ * K-steps (32 gathered B rows each) every workgroup tile walks, for judging the balance of the
+ * schedule: the tiles in launch order of their classes, then the column-gathered slabs, then the
+ * panels.  Returns their number; fills out[0 .. min(number, cap) - 1] when out is not NULL.
+ */
+int64_t vbr_get_tile_ksteps(const vbr_t *v, int64_t *out, int64_t cap);
+
 void vbr_free(vbr_t *v);
 
 /*

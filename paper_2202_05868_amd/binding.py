@@ -20,7 +20,7 @@ _DTYPES = {"f16": VBR_F16, "bf16": VBR_BF16}
 EXPORTS = ("sa1_reorder", "vbr_build", "vbr_get_index", "vbr_unpack_block", "vbr_device_bytes",
            "vbr_upload", "vbr_spmm", "vbr_get_schedule", "vbr_free", "vbr_strerror",
            "vbr_last_hip_error", "sa1_blocking_curve", "csr_spmm_create", "csr_device_bytes", "csr_upload",
-           "csr_spmm", "csr_free", "vbr_probe_launch", "vbr_get_launches", "vbr_audit")
+           "csr_spmm", "csr_free", "vbr_probe_launch", "vbr_get_launches", "vbr_audit", "vbr_get_tile_ksteps")
 
 
 class VbrError(RuntimeError):
@@ -60,6 +60,8 @@ def _load():
     lib.vbr_get_schedule.argtypes = [vp, P(i64), P(i64), P(i64)]
     lib.vbr_get_launches.argtypes = [vp, i64, P(i32), vp, vp, vp]
     lib.vbr_get_launches.restype = ctypes.c_int
+    lib.vbr_get_tile_ksteps.argtypes = [vp, vp, i64]
+    lib.vbr_get_tile_ksteps.restype = i64
     lib.vbr_audit.argtypes = [vp]
     lib.vbr_audit.restype = ctypes.c_int
     lib.vbr_free.argtypes = [vp]
@@ -214,6 +216,13 @@ class Vbr:
         if rc != 0:
             raise VbrError(rc, "vbr_unpack_block")
         return out
+
+    def tile_ksteps(self) -> np.ndarray:
+        """K-steps of every workgroup tile of the schedule (tiles, column-gathered slabs, panels)."""
+        n = int(_lib.vbr_get_tile_ksteps(self._h, None, 0))
+        out = np.zeros(max(n, 1), dtype=np.int64)
+        _lib.vbr_get_tile_ksteps(self._h, out.ctypes.data_as(ctypes.c_void_p), n)
+        return out[:n]
 
     def audit(self) -> None:
         """Raise unless every index the kernels use lies inside what it indexes."""

@@ -30,6 +30,7 @@ inline bool use_panels(int lg_gran, int64_t short_rows) { return lg_gran >= 3 &&
 // and up to 8 fragments (8 loads) per 128 columns; a one-slab tile 32 B rows x 256 columns (16 loads)
 // and one fragment.  The direct-to-LDS load instruction is the unit of cost of both kernels.
 constexpr int64_t kPanelStepCost = 32, kTileStepCost = 17;
+constexpr int64_t kSlabMaxCols = 1024;       // columns a slab of low rows gathers before the next group starts a new slab
 
 int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups, int32_t G,
                int32_t col_block, vbr *v)
@@ -134,13 +135,14 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     // The order of the low groups in the low-row list is free (C is written through the row list).
     // Slabs cut from a list in which groups with similar block patterns follow each other gather
     // far fewer B rows, so the list is built cluster by cluster: the first group not yet placed
-    // leads a cluster and takes with it every later group whose block set has a Jaccard similarity
-    // of at least 1/4 with the LEADER'S set (no pattern update: this only orders the packing, the
-    // blocking is the caller's).  Candidates come from an index column block -> low groups.  When
+    // leads a cluster and takes with it every later group that shares at least half of the smaller
+    // of the two block sets with the LEADER (overlap coefficient >= 1/2, which unlike the Jaccard
+    // similarity does not fade when both sets carry noise blocks of their own; no pattern update:
+    // this only orders the packing, the blocking is the caller's).  Candidates come from an index column block -> low groups.  When
     // the first 512 leaders find next to nothing (unstructured matrices), the rest keeps its order.
     {
         const int64_t n_low = (int64_t)low_groups.size();
-        std::vector<int32_t> order;
+        std::vector<int32_t> order, cluster_first;      // cluster_first: index in `order` of every cluster's leader
         order.reserve((size_t)n_low);
         std::vector<int64_t> inv_ptr((size_t)KB + 1, 0);
         for (const int32_t g : low_groups)
@@ -162,6 +164,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         for (int64_t i = 0; i < n_low; ++i) {
             if (placed[i]) continue;
             placed[i] = 1;
+            cluster_first.push_back((int32_t)order.size());
             order.push_back((int32_t)i);
             if (!clustering) continue;
             const int32_t g = low_groups[i];
@@ -179,22 +182,53 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             std::sort(hit.begin(), hit.end());
             for (const int32_t j : hit) {
                 const int32_t gj = low_groups[j];
-                const int64_t I = cnt[j], U = li + (v->blk_ptr[gj + 1] - v->blk_ptr[gj]) - I;
+                const int64_t I = cnt[j], lj = v->blk_ptr[gj + 1] - v->blk_ptr[gj];
                 cnt[j] = 0;
-                if (4 * I >= U) { placed[j] = 1; order.push_back(j); ++followers; }
+                if (2 * I >= std::min(li, lj)) { placed[j] = 1; order.push_back(j); ++followers; }
             }
             if (++leaders == 512 && followers < 64) clustering = false;
         }
-        for (const int32_t i : order) {
-            const int32_t g = low_groups[i];
-            v->group_prow[g] = (int32_t)v->prow.size();
-            for (int64_t q = row_groups[g]; q < row_groups[g + 1]; ++q) v->prow.push_back(perm[q]);
+        // A cluster of two slabs' worth of rows or more begins and ends on a slab boundary (the list is
+        // padded with -1: positions without a row), so that no slab mixes it with its neighbours.  And no
+        // slab gathers more than kSlabMaxCols columns if it can be helped: a group whose columns would
+        // take the slab beyond that starts a new slab (unrelated rows add up their columns, and the
+        // longest slab of a launch, one workgroup per column tile, is what the launch waits for).
+        cluster_first.push_back((int32_t)order.size());
+        std::vector<int64_t> col_slab((size_t)std::max<int64_t>(csr->n_cols, 1), -1);   // slab that last counted the column
+        int64_t slab_id = 0, slab_cols = 0;
+        auto pad_to_slab = [&]() {
+            while (v->prow.size() % kSlabRows != 0) v->prow.push_back(-1);
+            ++slab_id;
+            slab_cols = 0;
+        };
+        for (size_t c = 0; c + 1 < cluster_first.size(); ++c) {
+            int64_t rows = 0;
+            for (int32_t o = cluster_first[c]; o < cluster_first[c + 1]; ++o)
+                rows += row_groups[low_groups[order[o]] + 1] - row_groups[low_groups[order[o]]];
+            const bool align = rows >= 2 * kSlabRows;
+            if (align) pad_to_slab();
+            for (int32_t o = cluster_first[c]; o < cluster_first[c + 1]; ++o) {
+                const int32_t g = low_groups[order[o]];
+                int64_t fresh = 0;                      // columns of the group the current slab does not hold yet
+                for (int64_t q = row_groups[g]; q < row_groups[g + 1]; ++q)
+                    for (int64_t p = csr->row_ptr[perm[q]]; p < csr->row_ptr[perm[q] + 1]; ++p)
+                        fresh += col_slab[csr->col_idx[p]] != slab_id;
+                if (v->prow.size() % kSlabRows != 0 && slab_cols + fresh > kSlabMaxCols) pad_to_slab();
+                v->group_prow[g] = (int32_t)v->prow.size();
+                for (int64_t q = row_groups[g]; q < row_groups[g + 1]; ++q) {
+                    if (v->prow.size() % kSlabRows == 0) { ++slab_id; slab_cols = 0; }      // a new slab begins here
+                    for (int64_t p = csr->row_ptr[perm[q]]; p < csr->row_ptr[perm[q] + 1]; ++p)
+                        if (col_slab[csr->col_idx[p]] != slab_id) { col_slab[csr->col_idx[p]] = slab_id; ++slab_cols; }
+                    v->prow.push_back(perm[q]);
+                }
+            }
+            if (align) pad_to_slab();
         }
     }
 
     // pass 2: the low rows, in chunks of 8 slabs.
     const int64_t n_prows = (int64_t)v->prow.size();
-    std::vector<int32_t> prow_group((size_t)n_prows);
+    std::vector<int32_t> prow_group((size_t)n_prows, -1);     // -1: a padding position
     for (int32_t g = 0; g < G; ++g)
         if (v->group_prow[g] >= 0)
             for (int64_t i = 0; i < row_groups[g + 1] - row_groups[g]; ++i) prow_group[v->group_prow[g] + i] = g;
@@ -220,7 +254,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         blocks.clear();
         for (int64_t i = i0; i < i1; ++i) {
             const int32_t g = prow_group[i];
-            if (i > i0 && prow_group[i - 1] == g) continue;
+            if (g < 0 || (i > i0 && prow_group[i - 1] == g)) continue;
             for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b)
                 if (pos_of_block[v->blk_col[b]] < 0) { pos_of_block[v->blk_col[b]] = 0; blocks.push_back(v->blk_col[b]); }
         }
@@ -230,6 +264,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         blk_mask.assign((size_t)nu, 0u);
         for (int64_t i = i0; i < i1; ++i) {
             const int32_t g = prow_group[i];
+            if (g < 0) continue;
             const uint32_t bit = 1u << ((i - i0) / kSlabRows);
             for (int64_t b = v->blk_ptr[g]; b < v->blk_ptr[g + 1]; ++b) blk_mask[pos_of_block[v->blk_col[b]]] |= bit;
         }
@@ -280,6 +315,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         // size, after the last panel.
         for (int64_t i = i0; i < i1; ++i) {
             const int64_t r = v->prow[i];
+            if (r < 0) continue;
             const int s = (int)((i - i0) / kSlabRows), mrow = (int)((i - i0) % kSlabRows);
             for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
                 const int64_t c = csr->col_idx[p];
@@ -306,6 +342,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             cols.clear();
             for (int64_t i = s0; i < s1; ++i) {
                 const int64_t r = v->prow[i];
+                if (r < 0) continue;
                 for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p)
                     if (pos_of_col[csr->col_idx[p]] < 0) { pos_of_col[csr->col_idx[p]] = 0; cols.push_back(csr->col_idx[p]); }
             }
@@ -324,6 +361,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             const int64_t stride = tile_kstep_stride(td.n_rows, 1);
             for (int64_t i = s0; i < s1; ++i) {
                 const int64_t r = v->prow[i];
+                if (r < 0) continue;
                 for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
                     const int64_t k = pos_of_col[csr->col_idx[p]];
                     fill_dst.push_back(a_units * 8 + (k / kStepK) * stride + frag_index((int)(i - s0), (int)(k % kStepK), td.n_rows));
@@ -350,6 +388,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
                 cols.clear();
                 for (int64_t i = s0; i < std::min(i1, s0 + kSlabRows); ++i) {
                     const int64_t r = v->prow[i];
+                    if (r < 0) continue;
                     for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
                         const int32_t c = csr->col_idx[p];
                         if (pos_of_col[c] < 0) { pos_of_col[c] = 0; cols.push_back(c); }
@@ -591,7 +630,7 @@ extern "C" int vbr_audit(const vbr_t *v)
         }
     }
     for (const int32_t r : v->prow)
-        if (r < 0 || r >= M) return VBR_EINVAL;
+        if (r < -1 || r >= M) return VBR_EINVAL;          // -1: a padding position, never stored
     for (const PanelDesc &pd : v->panels) {
         if (pd.n_rows < 1 || pd.n_rows > kPanelSlabs * kSlabRows) return VBR_EINVAL;
         if (pd.row_begin < 0 || (int64_t)pd.row_begin + pd.n_rows > (int64_t)v->prow.size()) return VBR_EINVAL;
@@ -700,6 +739,18 @@ extern "C" int vbr_get_schedule(const vbr_t *v, int64_t *n_tiles, int64_t *n_kst
     if (n_ksteps) *n_ksteps = v->ks_ptr.back() + (int64_t)v->pk_mask.size() + (int64_t)v->gcol.size() / vbrk::kStepK;
     if (packed_elems) *packed_elems = (int64_t)v->vals.size();
     return VBR_OK;
+}
+
+extern "C" int64_t vbr_get_tile_ksteps(const vbr_t *v, int64_t *out, int64_t cap)
+{
+    if (!v) return VBR_EINVAL;
+    const int64_t n = (int64_t)(v->tiles.size() + v->gtiles.size() + v->panels.size());
+    if (!out) return n;
+    int64_t w = 0;
+    for (const vbrk::TileDesc &t : v->tiles) { if (w < cap) out[w] = t.n_ks; ++w; }
+    for (const vbrk::TileDesc &t : v->gtiles) { if (w < cap) out[w] = t.n_ks; ++w; }
+    for (const vbrk::PanelDesc &t : v->panels) { if (w < cap) out[w] = t.n_ks; ++w; }
+    return n;
 }
 
 extern "C" void vbr_free(vbr_t *v) { delete v; }

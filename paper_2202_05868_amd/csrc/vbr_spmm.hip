@@ -41,6 +41,7 @@ struct Params {
     const int32_t *prow;      // ... and the list of the low rows their row positions refer to
     const uint16_t *vals;
     const uint16_t *zeros;    // 256 zero bytes: source of padding rows, padding lanes and columns >= N
+    const uint16_t *zfrag;    // 1 KiB of zeros behind the last fragment: padding rows of the column-gathered tiles
     const uint16_t *B;
     float *C;
     int64_t ldb, ldc;
@@ -133,6 +134,7 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
     const lds_u8_ptr sm = (lds_u8_ptr)smem;
     const uint32_t smem_base = (uint32_t)(uintptr_t)sm;      // LDS byte address, for M0
     const char *zeros = reinterpret_cast<const char *>(p.zeros);
+    const char *zpad = reinterpret_cast<const char *>(p.zfrag);
     const int n_ks = td.n_ks;
     const int q = lane >> 4, s16 = lane & 15;
 
@@ -161,11 +163,13 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         uint32_t b_col[4];       // byte offset of this lane's chunk from the tile's first column
         uint32_t b_lane[4];      // fast path: offset of this lane's 16 bytes from the first row of the wave's granule
         bool b_col_ok[4];
+        uint32_t b_coff[4];      // column-gathered tiles: the same, clamped to the tile's last existing chunk
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int chunk = (lane & 31) ^ (2 * (2 * i + half));
             b_col[i] = chunk * 16;
             b_col_ok[i] = chunk <= last_chunk;
+            b_coff[i] = (uint32_t)(chunk <= last_chunk ? chunk : last_chunk) * 16;      // past column N: the last chunk again
             b_lane[i] = (uint32_t)((8 * wave + 2 * i + half) & gmask) * ldb_bytes + (chunk <= last_chunk ? chunk : last_chunk) * 16;
         }
 
@@ -208,7 +212,9 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         Rows rb0, rb1;
         rb0.r[0] = rb1.r[0] = -1;
         auto load_rows = [&](int ks) -> Rows {
-            const int kc = ks < n_ks ? ks : n_ks - 1;      // past the end: reload the last K-step (never computed)
+            // past the end: reload the last K-step (never computed); wave-uniform, and said so, or the
+            // lookups below become vector loads, which cost the load path as much as a load of B
+            const int kc = __builtin_amdgcn_readfirstlane(ks < n_ks ? ks : n_ks - 1);
             Rows out;
             if constexpr (GATHER) {
                 const const_i32_ptr src = (const_i32_ptr)p.gcol + ((int64_t)td.ks_begin + kc) * kStepK + 8 * wave;
@@ -222,12 +228,15 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         auto issue_b = [&](int ks, int slot) {
             const uint32_t sb = smem_base + slot * kPanelBytes + 8 * wave * kRowBytes;
             if constexpr (GATHER) {
+                // the two row pointers of a load are computed on the scalar unit (a padding entry points
+                // at the kilobyte of zeros behind the values); a lane only selects its half's pointer and
+                // adds its column offset
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int e = half ? rb0.r[2 * i + 1] : rb0.r[2 * i];
-                    // chunks at or beyond column N re-read the tile's last existing chunk, as on the fast path
-                    const char *src = e >= 0 ? Btile + (uint64_t)(uint32_t)e * ldb_bytes + (b_col_ok[i] ? b_col[i] : (uint32_t)last_chunk * 16) : zeros;
-                    dma16(src, sb + 2 * i * kRowBytes);
+                    const int e0 = rb0.r[2 * i], e1 = rb0.r[2 * i + 1];
+                    const char *p0 = e0 >= 0 ? Btile + (uint64_t)(uint32_t)e0 * ldb_bytes : zpad;
+                    const char *p1 = e1 >= 0 ? Btile + (uint64_t)(uint32_t)e1 * ldb_bytes : zpad;
+                    dma16((half ? p1 : p0) + b_coff[i], sb + 2 * i * kRowBytes);
                 }
             } else if (tile_fast && rb0.r[0] >= 0) {
                 const char *rowptr = Btile + (uint64_t)(uint32_t)rb0.r[0] * ldb_bytes;          // scalar, 64-bit
@@ -347,8 +356,8 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
 #pragma unroll
     for (int s = 0; s < S; ++s) {
         const int rr = s * kSlabRows + s16;
-        if (rr < td.n_rows) {
-            const int64_t orig = (GATHER ? p.prow : p.perm)[td.row_begin + rr];
+        const int64_t orig = rr < td.n_rows ? (GATHER ? p.prow : p.perm)[td.row_begin + rr] : -1;
+        if (orig >= 0) {                 // a position of the low-row list may be padding (-1)
             float *crow = p.C + orig * p.ldc;
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
@@ -575,8 +584,8 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
 #pragma unroll
     for (int s = 0; s < HS; ++s) {
         const int rr = (wr * HS + s) * kSlabRows + s16;
-        if (rr < pd.n_rows) {
-            const int64_t orig = p.prow[pd.row_begin + rr];
+        const int64_t orig = rr < pd.n_rows ? p.prow[pd.row_begin + rr] : -1;
+        if (orig >= 0) {                 // a position of the low-row list may be padding (-1)
             float *crow = p.C + orig * p.ldc;
 #pragma unroll
             for (int f = 0; f < 2; ++f) {
@@ -715,6 +724,7 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     pp.n_panels = (int32_t)v->panels.size();
     pp.n_ntiles = (int32_t)((N + 127) / 128);
     p.gcol = reinterpret_cast<const int32_t *>(d + v->lay.gcol_off);
+    p.zfrag = pp.zfrag;
     p.prow = pp.prow;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return v->dtype == VBR_F16 ? vbrk::launch_all<VBR_F16>(v, p, pp, stream) : vbrk::launch_all<VBR_BF16>(v, p, pp, stream);
