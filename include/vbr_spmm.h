@@ -13,7 +13,7 @@
  *                 only the nonzero blocks, zero-filled (section 2, section 3.1 last paragraph).
  *   vbr_spmm      C = A.B, every stored block multiplied as a small dense product on the
  *                 matrix units (section 4.4.1), in one launch per kernel class the matrix
- *                 needs (at most six: see vbr_get_launches below).
+ *                 needs (at most nine: see vbr_get_launches below).
  *
  * sa1_reorder and vbr_build are deterministic integer host code.  vbr_spmm runs on the GPU.
  * All pointers are HOST pointers unless the name ends in _dev.  Nothing is retained from the
@@ -147,16 +147,18 @@ int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64
  * 128 at a time, by the panel kernel (their slabs of 16 rows share the B rows of the union of their
  * column blocks) or by the tile kernel on column-gathered slabs (every slab loads exactly the B rows
  * of the columns its rows touch), whichever packing needs fewer loads; the other groups by the tile
- * kernel, either in one launch per class of tile
+ * kernel, on whole column blocks or, where the blocks are mostly fill-in, on the columns the rows
+ * of a tile touch (VBR_LAUNCH_GATHER_*), either in one launch per class of tile
  * height that occurs (1, 2, 3-4, 5-8 slabs of 16 rows) or, for small matrices, in one launch that
  * mixes the classes: between 0 and VBR_MAX_LAUNCHES launches.  kinds / tiles / workgroups (each
  * room for VBR_MAX_LAUNCHES entries, any may be NULL) receive the kernel, the number of row tiles
  * or panels, and the grid size of each launch.
  */
-enum { VBR_MAX_LAUNCHES = 6 };
+enum { VBR_MAX_LAUNCHES = 9 };
 enum {
     VBR_LAUNCH_PANEL = 0, VBR_LAUNCH_TILE_1 = 1, VBR_LAUNCH_TILE_2 = 2, VBR_LAUNCH_TILE_4 = 3,
-    VBR_LAUNCH_TILE_8 = 4, VBR_LAUNCH_TILE_MIXED = 5, VBR_LAUNCH_GATHER = 6
+    VBR_LAUNCH_TILE_8 = 4, VBR_LAUNCH_TILE_MIXED = 5,
+    VBR_LAUNCH_GATHER_1 = 6, VBR_LAUNCH_GATHER_2 = 7, VBR_LAUNCH_GATHER_4 = 8, VBR_LAUNCH_GATHER_8 = 9
 };
 int vbr_get_launches(const vbr_t *v, int64_t N, int32_t *n_launches, int32_t *kinds, int64_t *tiles,
                      int64_t *workgroups);

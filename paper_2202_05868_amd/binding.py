@@ -195,13 +195,14 @@ class Vbr:
 
     LAUNCH_KINDS = ("vbr_spmm_panel_kernel", "vbr_spmm_kernel<1 slab>", "vbr_spmm_kernel<2 slabs>",
                     "vbr_spmm_kernel<4 slabs>", "vbr_spmm_kernel<8 slabs>", "vbr_spmm_mixed_kernel",
-                    "vbr_spmm_kernel<1 slab, column-gathered>")
+                    "vbr_spmm_kernel<1 slab, column-gathered>", "vbr_spmm_kernel<2 slabs, column-gathered>",
+                    "vbr_spmm_kernel<4 slabs, column-gathered>", "vbr_spmm_kernel<8 slabs, column-gathered>")
 
     def launches(self, n: int) -> list:
         """The kernel launches one ``spmm`` with dense width ``n`` issues, from the library's plan."""
-        kinds = np.zeros(8, dtype=np.int32)
-        tiles = np.zeros(8, dtype=np.int64)
-        wgs = np.zeros(8, dtype=np.int64)
+        kinds = np.zeros(16, dtype=np.int32)
+        tiles = np.zeros(16, dtype=np.int64)
+        wgs = np.zeros(16, dtype=np.int64)
         cnt = ctypes.c_int32(0)
         rc = _lib.vbr_get_launches(self._h, int(n), ctypes.byref(cnt), kinds.ctypes.data_as(ctypes.c_void_p),
                                    tiles.ctypes.data_as(ctypes.c_void_p), wgs.ctypes.data_as(ctypes.c_void_p))

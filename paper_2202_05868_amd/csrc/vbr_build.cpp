@@ -30,6 +30,7 @@ inline bool use_panels(int lg_gran, int64_t short_rows) { return lg_gran >= 3 &&
 // and up to 8 fragments (8 loads) per 128 columns; a one-slab tile 32 B rows x 256 columns (16 loads)
 // and one fragment.  The direct-to-LDS load instruction is the unit of cost of both kernels.
 constexpr int64_t kPanelStepCost = 32, kTileStepCost = 17;
+constexpr int64_t kTileMaxGatherSteps = 64;  // K-steps a column-gathered tile of several slabs may walk before it is cut in two
 constexpr int64_t kSlabMaxCols = 1024;       // columns a slab of low rows gathers before the next group starts a new slab
 
 int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_groups, int32_t G,
@@ -66,6 +67,9 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     std::vector<int32_t> pos_of_block((size_t)std::max<int64_t>(KB, 1), -1);
     std::vector<int32_t> blocks;
     std::vector<int32_t> low_groups;            // groups lower than a slab, in group order
+    std::vector<int32_t> tall_gathered;         // taller groups whose tiles gather single columns
+    std::vector<int64_t> col_stamp((size_t)std::max<int64_t>(csr->n_cols, 1), -1);
+    int64_t col_stamp_id = 0;
     std::vector<TileDesc> tiles;
     int64_t a_units = 0;   // running size of the packed values, in units of 8 values
 
@@ -104,6 +108,30 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
 
         const int64_t Kg = nb * col_block;
         const int64_t n_ks = (Kg + kStepK - 1) / kStepK;
+        const int64_t slabs = (h + kSlabRows - 1) / kSlabRows;
+        const int64_t nt = (slabs + kMaxSlabs - 1) / kMaxSlabs;
+        // Blocks with much fill-in hold many columns without a single entry.  When the columns the
+        // rows of the group's tiles actually touch need at most two thirds of the K-steps of its whole
+        // blocks, the tiles gather those columns instead (a gathered load costs the load path about
+        // a third more than a load of whole blocks); they are packed after the low rows, below.
+        {
+            int64_t gather_ks = 0, row = 0;
+            for (int64_t t = 0; t < nt; ++t) {
+                const int64_t s = slabs / nt + (t < slabs % nt ? 1 : 0);
+                const int64_t n_rows = std::min<int64_t>(s * kSlabRows, h - row);
+                ++col_stamp_id;
+                int64_t cols_t = 0;
+                for (int64_t q = r0 + row; q < r0 + row + n_rows; ++q)
+                    for (int64_t p = csr->row_ptr[perm[q]]; p < csr->row_ptr[perm[q] + 1]; ++p)
+                        if (col_stamp[csr->col_idx[p]] != col_stamp_id) { col_stamp[csr->col_idx[p]] = col_stamp_id; ++cols_t; }
+                gather_ks += (cols_t + kStepK - 1) / kStepK;
+                row += n_rows;
+            }
+            if (3 * gather_ks <= 2 * nt * n_ks) {
+                tall_gathered.push_back(g);
+                continue;
+            }
+        }
         if (v->ks_ptr[g] + n_ks > INT32_MAX / 64) return VBR_EINVAL;
         v->ks_ptr[g + 1] = v->ks_ptr[g] + n_ks;
         for (int64_t e = 0; e < n_ks * per_step; ++e) {
@@ -112,8 +140,6 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
             else v->krow.push_back(-1);
         }
 
-        const int64_t slabs = (h + kSlabRows - 1) / kSlabRows;
-        const int64_t nt = (slabs + kMaxSlabs - 1) / kMaxSlabs;
         v->group_first_tile[g + 1] = v->group_first_tile[g] + nt;
         int64_t row = 0;
         for (int64_t t = 0; t < nt; ++t) {
@@ -331,48 +357,56 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         return VBR_OK;
     };
 
-    // the slabs of a chunk as column-gathered tiles: K of a slab = the ascending list of the columns
-    // its rows touch, cut into K-steps of 32
+    // A column-gathered tile over the positions [s0, s1) of the low-row list (up to 8 slabs): its K
+    // dimension is the ascending list of the columns its rows touch, cut into K-steps of 32.
+    auto emit_gather_tile = [&](int64_t s0, int64_t s1, int32_t group_code) -> int {
+        cols.clear();
+        for (int64_t i = s0; i < s1; ++i) {
+            const int64_t r = v->prow[i];
+            if (r < 0) continue;
+            for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p)
+                if (pos_of_col[csr->col_idx[p]] < 0) { pos_of_col[csr->col_idx[p]] = 0; cols.push_back(csr->col_idx[p]); }
+        }
+        std::sort(cols.begin(), cols.end());
+        for (size_t k = 0; k < cols.size(); ++k) pos_of_col[cols[k]] = (int32_t)k;
+        const int64_t n_ks = ((int64_t)cols.size() + kStepK - 1) / kStepK;
+        if (g_ks + n_ks > INT32_MAX / 64) return VBR_EINVAL;
+        TileDesc td;
+        td.ks_begin = (int32_t)g_ks;
+        td.n_ks = (int32_t)n_ks;
+        td.a_off = a_units;
+        td.row_begin = (int32_t)s0;
+        td.n_rows = (int32_t)(s1 - s0);
+        td.n_slabs = (int32_t)((s1 - s0 + kSlabRows - 1) / kSlabRows);
+        td.group = group_code;
+        const int64_t stride = tile_kstep_stride(td.n_rows, td.n_slabs);
+        const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
+        for (int64_t i = s0; i < s1; ++i) {
+            const int64_t r = v->prow[i];
+            if (r < 0) continue;
+            const int slab = (int)((i - s0) / kSlabRows), m = (int)((i - s0) % kSlabRows);
+            const int rows = slab == td.n_slabs - 1 ? rows_last : kSlabRows;
+            for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
+                const int64_t k = pos_of_col[csr->col_idx[p]];
+                fill_dst.push_back(a_units * 8 + (k / kStepK) * stride + (int64_t)slab * kFragElems + frag_index(m, (int)(k % kStepK), rows));
+                fill_src.push_back(p);
+            }
+        }
+        for (int64_t k = 0; k < n_ks * kStepK; ++k) v->gcol.push_back(k < (int64_t)cols.size() ? cols[k] : -1);
+        for (const int32_t c : cols) pos_of_col[c] = -1;
+        a_units += n_ks * stride / 8;
+        g_ks += n_ks;
+        v->gtiles.push_back(td);
+        return VBR_OK;
+    };
+    // the slabs of a chunk of low rows as column-gathered tiles
     auto emit_gather = [&](int64_t pn) -> int {
         const int64_t i0 = pn * panel_rows, i1 = std::min(n_prows, i0 + panel_rows);
         v->chunk_gather[pn] = 1;
         v->chunk_index[pn] = (int32_t)v->gtiles.size();
         for (int64_t s0 = i0; s0 < i1; s0 += kSlabRows) {
-            const int64_t s1 = std::min(i1, s0 + kSlabRows);
-            cols.clear();
-            for (int64_t i = s0; i < s1; ++i) {
-                const int64_t r = v->prow[i];
-                if (r < 0) continue;
-                for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p)
-                    if (pos_of_col[csr->col_idx[p]] < 0) { pos_of_col[csr->col_idx[p]] = 0; cols.push_back(csr->col_idx[p]); }
-            }
-            std::sort(cols.begin(), cols.end());
-            for (size_t k = 0; k < cols.size(); ++k) pos_of_col[cols[k]] = (int32_t)k;
-            const int64_t n_ks = ((int64_t)cols.size() + kStepK - 1) / kStepK;
-            if (g_ks + n_ks > INT32_MAX / 64) return VBR_EINVAL;
-            TileDesc td;
-            td.ks_begin = (int32_t)g_ks;
-            td.n_ks = (int32_t)n_ks;
-            td.a_off = a_units;
-            td.row_begin = (int32_t)s0;
-            td.n_rows = (int32_t)(s1 - s0);
-            td.n_slabs = 1;
-            td.group = -1;
-            const int64_t stride = tile_kstep_stride(td.n_rows, 1);
-            for (int64_t i = s0; i < s1; ++i) {
-                const int64_t r = v->prow[i];
-                if (r < 0) continue;
-                for (int64_t p = csr->row_ptr[r]; p < csr->row_ptr[r + 1]; ++p) {
-                    const int64_t k = pos_of_col[csr->col_idx[p]];
-                    fill_dst.push_back(a_units * 8 + (k / kStepK) * stride + frag_index((int)(i - s0), (int)(k % kStepK), td.n_rows));
-                    fill_src.push_back(p);
-                }
-            }
-            for (int64_t k = 0; k < n_ks * kStepK; ++k) v->gcol.push_back(k < (int64_t)cols.size() ? cols[k] : -1);
-            for (const int32_t c : cols) pos_of_col[c] = -1;
-            a_units += n_ks * stride / 8;
-            g_ks += n_ks;
-            v->gtiles.push_back(td);
+            const int rc = emit_gather_tile(s0, std::min(i1, s0 + kSlabRows), -1);
+            if (rc != VBR_OK) return rc;
         }
         return VBR_OK;
     };
@@ -405,6 +439,49 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
         }
         const int rc = gather ? emit_gather(pn) : emit_panel(pn);
         if (rc != VBR_OK) return rc;
+    }
+
+    // the tiles of the tall groups that gather single columns: their rows follow the low rows in the row list
+    v->group_gt_first.assign((size_t)std::max<int32_t>(G, 1), -1);
+    for (const int32_t g : tall_gathered) {
+        const int64_t r0 = row_groups[g], h = row_groups[g + 1] - r0;
+        const int64_t slabs = (h + kSlabRows - 1) / kSlabRows;
+        const int64_t nt = (slabs + kMaxSlabs - 1) / kMaxSlabs;
+        v->group_gt_first[g] = (int32_t)v->gtiles.size();
+        // A tile whose rows touch more than kTileMaxGatherSteps K-steps' worth of columns is cut in two
+        // (at a slab boundary; a single slab into two partial ones): fewer rows share each gathered B row,
+        // but the longest tile of a launch, one workgroup per column tile, is what the launch waits for.
+        struct Range { int64_t q0, q1; };
+        std::vector<Range> todo;
+        int64_t row = 0;
+        for (int64_t t = 0; t < nt; ++t) {
+            const int64_t s = slabs / nt + (t < slabs % nt ? 1 : 0);
+            const int64_t n_rows = std::min<int64_t>(s * kSlabRows, h - row);
+            todo.push_back(Range{r0 + row, r0 + row + n_rows});
+            row += n_rows;
+        }
+        for (size_t i = 0; i < todo.size(); ++i) {          // in row order: a cut tile is replaced by its halves in place
+            const Range rg_ = todo[i];
+            const int64_t n_rows = rg_.q1 - rg_.q0, n_slabs = (n_rows + kSlabRows - 1) / kSlabRows;
+            if (n_rows > 1) {
+                ++col_stamp_id;
+                int64_t cols_t = 0;
+                for (int64_t q = rg_.q0; q < rg_.q1; ++q)
+                    for (int64_t p = csr->row_ptr[perm[q]]; p < csr->row_ptr[perm[q] + 1]; ++p)
+                        if (col_stamp[csr->col_idx[p]] != col_stamp_id) { col_stamp[csr->col_idx[p]] = col_stamp_id; ++cols_t; }
+                if (cols_t > kTileMaxGatherSteps * kStepK) {
+                    const int64_t mid = n_slabs > 1 ? rg_.q0 + (n_slabs / 2) * kSlabRows : rg_.q0 + n_rows / 2;
+                    todo[i] = Range{rg_.q0, mid};
+                    todo.insert(todo.begin() + (int64_t)i + 1, Range{mid, rg_.q1});
+                    --i;
+                    continue;
+                }
+            }
+            const int64_t s0 = (int64_t)v->prow.size();
+            for (int64_t q = rg_.q0; q < rg_.q1; ++q) v->prow.push_back(perm[q]);
+            const int rc = emit_gather_tile(s0, s0 + n_rows, -2 - g);
+            if (rc != VBR_OK) return rc;
+        }
     }
 
     // pass 3: the values.  One allocation: tiles' fragments, panels' fragments, and one fragment
@@ -455,6 +532,25 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     }
     for (int c = 0; c < 4; ++c) v->class_begin[c + 1] += v->class_begin[c];
 
+    // the gathered tiles as the device holds them: by slab class, heaviest first
+    {
+        const int64_t NG = (int64_t)v->gtiles.size();
+        std::vector<int32_t> gorder(NG);
+        for (int64_t i = 0; i < NG; ++i) gorder[i] = (int32_t)i;
+        std::stable_sort(gorder.begin(), gorder.end(), [&](int32_t a, int32_t b) {
+            const int ca = slab_class(v->gtiles[a].n_slabs), cb = slab_class(v->gtiles[b].n_slabs);
+            if (ca != cb) return ca < cb;
+            return (int64_t)v->gtiles[a].n_ks * v->gtiles[a].n_slabs > (int64_t)v->gtiles[b].n_ks * v->gtiles[b].n_slabs;
+        });
+        v->gtiles_dev.resize(NG);
+        for (int c = 0; c < 5; ++c) v->gclass_begin[c] = 0;
+        for (int64_t i = 0; i < NG; ++i) {
+            v->gtiles_dev[i] = v->gtiles[gorder[i]];
+            v->gclass_begin[slab_class(v->gtiles[gorder[i]].n_slabs) + 1]++;
+        }
+        for (int c = 0; c < 4; ++c) v->gclass_begin[c + 1] += v->gclass_begin[c];
+    }
+
     DeviceLayout &L = v->lay;
     L.zeros_off = 0;                   // 256 zero bytes the kernel reads for padding
     L.tiles_off = 256;
@@ -463,7 +559,7 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
     L.panels_off = align_up(L.perm_off + M * 4, 256);
     L.pk_meta_off = align_up(L.panels_off + (int64_t)v->panels.size() * (int64_t)sizeof(PanelDesc), 256);
     L.prow_off = align_up(L.pk_meta_off + (int64_t)v->pk_meta.size() * 4, 256);
-    L.gcol_off = align_up(L.prow_off + n_prows * 4, 256);
+    L.gcol_off = align_up(L.prow_off + (int64_t)v->prow.size() * 4, 256);
     L.vals_off = align_up(L.gcol_off + (int64_t)v->gcol.size() * 4, 256);
     L.total = std::max<int64_t>(256, align_up(L.vals_off + (int64_t)v->vals.size() * 2, 256));
     return VBR_OK;
@@ -572,6 +668,31 @@ extern "C" int vbr_unpack_block(const vbr_t *v, int64_t blk, void *dst_)
         }
         return VBR_OK;
     }
+    if (v->group_gt_first[g] >= 0) {
+        // tall group whose tiles gather single columns: the tiles follow each other, each with its own column list
+        const int64_t h = v->row_groups[g + 1] - v->row_groups[g];
+        int64_t row = 0;
+        for (int64_t t = v->group_gt_first[g]; row < h; ++t) {
+            const TileDesc &td = v->gtiles[t];
+            const int32_t *cb0 = &v->gcol[(size_t)td.ks_begin * kStepK], *ce = cb0 + (size_t)td.n_ks * kStepK;
+            while (ce > cb0 && ce[-1] < 0) --ce;
+            const int64_t stride = tile_kstep_stride(td.n_rows, td.n_slabs);
+            const int rows_last = td.n_rows - (td.n_slabs - 1) * kSlabRows;
+            for (int32_t rr = 0; rr < td.n_rows; ++rr, ++row) {
+                const int slab = rr / kSlabRows, m = rr % kSlabRows;
+                const int rows = slab == td.n_slabs - 1 ? rows_last : kSlabRows;
+                for (int64_t c = 0; c < cb; ++c) {
+                    const int32_t col = (int32_t)((int64_t)v->blk_col[blk] * cb + c);
+                    const int32_t *it = std::lower_bound(cb0, ce, col);
+                    if (it == ce || *it != col) { dst[row * cb + c] = 0; continue; }          // fill-in: not stored
+                    const int64_t k = it - cb0;
+                    dst[row * cb + c] = v->vals[(size_t)td.a_off * 8 + (size_t)((k / kStepK) * stride) + (size_t)slab * kFragElems +
+                                                frag_index(m, (int)(k % kStepK), rows)];
+                }
+            }
+        }
+        return VBR_OK;
+    }
     int64_t row = 0;
     for (int64_t t = v->group_first_tile[g]; t < v->group_first_tile[g + 1]; ++t) {
         const TileDesc &td = v->tiles[v->tile_of_group_order[t]];
@@ -650,11 +771,15 @@ extern "C" int vbr_audit(const vbr_t *v)
     if ((int64_t)v->gcol.size() % kStepK != 0) return VBR_EINVAL;
     for (const int32_t c : v->gcol)
         if (c < -1 || c >= K) return VBR_EINVAL;
-    for (const TileDesc &td : v->gtiles) {
-        if (td.n_rows < 1 || td.n_rows > kSlabRows || td.n_slabs != 1) return VBR_EINVAL;
+    if (v->gtiles_dev.size() != v->gtiles.size() || v->gclass_begin[0] != 0 || v->gclass_begin[4] != (int32_t)v->gtiles.size()) return VBR_EINVAL;
+    for (int c = 0; c < 4; ++c)
+        for (int32_t t = v->gclass_begin[c]; t < v->gclass_begin[c + 1]; ++t)
+            if (slab_class(v->gtiles_dev[t].n_slabs) != c) return VBR_EINVAL;
+    for (const TileDesc &td : v->gtiles_dev) {
+        if (td.n_rows < 1 || td.n_slabs != (td.n_rows + kSlabRows - 1) / kSlabRows || td.n_slabs > kMaxSlabs || td.group >= 0) return VBR_EINVAL;
         if (td.row_begin < 0 || (int64_t)td.row_begin + td.n_rows > (int64_t)v->prow.size()) return VBR_EINVAL;
         if (td.n_ks < 0 || td.ks_begin < 0 || ((int64_t)td.ks_begin + td.n_ks) * kStepK > (int64_t)v->gcol.size()) return VBR_EINVAL;
-        if (td.a_off < 0 || td.a_off * 8 + (int64_t)td.n_ks * tile_kstep_stride(td.n_rows, 1) > n_vals - kFragElems) return VBR_EINVAL;
+        if (td.a_off < 0 || td.a_off * 8 + (int64_t)td.n_ks * tile_kstep_stride(td.n_rows, td.n_slabs) > n_vals - kFragElems) return VBR_EINVAL;
     }
     for (size_t i = v->vals.size() - kFragElems; i < v->vals.size(); ++i)
         if (v->vals[i] != 0) return VBR_EINVAL;                                               // the zero fragment
@@ -694,21 +819,25 @@ int plan_launches(const vbr *v, int64_t N, Launch out[VBR_MAX_LAUNCHES])
     const int64_t Qt = (N + kTileN - 1) / kTileN, Qp = (N + kPanelN - 1) / kPanelN;
     if (!v->panels.empty())
         out[n++] = Launch{VBR_LAUNCH_PANEL, 0, (int32_t)v->panels.size(), grid_size((int64_t)v->panels.size(), Qp)};
-    // Five tile classes, contiguous in the device's tile array: 1, 2, 3-4, 5-8 slabs, then the
-    // column-gathered slabs.  Several classes that together do not give every CU a few workgroups
-    // share one launch of the mixed kernel; otherwise every class present gets a launch of its own
-    // kernel, the gathered slabs first.  (Mixing only the small classes of a large matrix was
-    // measured and lost: the mixed kernel holds the LDS of the tallest class, and the tall tiles of the
-    // graph workload, few but with long block lists, ran 20 % longer in it.)
-    const int64_t T_low = (int64_t)v->gtiles.size();
-    int classes = T_low > 0 ? 1 : 0;
-    for (int c = 0; c < 4; ++c) classes += v->class_begin[c + 1] > v->class_begin[c];
-    const int64_t T_all = v->class_begin[4] + T_low;
+    // Eight tile classes, contiguous in the device's tile array: tiles of 1, 2, 3-4, 5-8 slabs that
+    // gather whole column blocks, then the same four of tiles that gather single columns.  Several
+    // classes that together do not give every CU a few workgroups share one launch of the mixed
+    // kernel; otherwise every class present gets a launch of its own kernel, the gathered ones first.
+    // (Mixing only the small classes of a large matrix was measured and lost: the mixed kernel holds
+    // the LDS of the tallest class, and the tall tiles of the graph workload, few but with long block
+    // lists, ran 20 % longer in it.)
+    const int32_t T_blk = v->class_begin[4];
+    int classes = 0;
+    for (int c = 0; c < 4; ++c) classes += (v->class_begin[c + 1] > v->class_begin[c]) + (v->gclass_begin[c + 1] > v->gclass_begin[c]);
+    const int64_t T_all = (int64_t)T_blk + v->gclass_begin[4];
     if (classes > 1 && T_all * Qt < 4096) {
         out[n++] = Launch{VBR_LAUNCH_TILE_MIXED, 0, (int32_t)T_all, grid_size(T_all, Qt)};
         return n;
     }
-    if (T_low > 0) out[n++] = Launch{VBR_LAUNCH_GATHER, v->class_begin[4], (int32_t)T_low, grid_size(T_low, Qt)};
+    for (int c = 0; c < 4; ++c) {
+        const int32_t T = v->gclass_begin[c + 1] - v->gclass_begin[c];
+        if (T > 0) out[n++] = Launch{VBR_LAUNCH_GATHER_1 + c, T_blk + v->gclass_begin[c], T, grid_size(T, Qt)};
+    }
     for (int c = 0; c < 4; ++c) {
         const int32_t T = v->class_begin[c + 1] - v->class_begin[c];
         if (T > 0) out[n++] = Launch{VBR_LAUNCH_TILE_1 + c, v->class_begin[c], T, grid_size(T, Qt)};

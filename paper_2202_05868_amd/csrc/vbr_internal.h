@@ -105,7 +105,11 @@ struct vbr {
     std::vector<int32_t> group_prow;     // [n_groups] first low-row position of a low group, -1 for the others
     std::vector<uint8_t> chunk_gather;   // [n_chunks] 1 = packed as column-gathered tiles, 0 = as a panel
     std::vector<int32_t> chunk_index;    // [n_chunks] index of its panel in `panels`, or of its first tile in `gtiles`
-    std::vector<vbrk::TileDesc> gtiles;   // column-gathered tiles: one slab each, row_begin = position in prow, group = -1
+    std::vector<vbrk::TileDesc> gtiles;   // column-gathered tiles in creation order: row_begin = position in prow; group = -1 for
+                                         // a slab of low rows, -2 - g for a tile of the tall group g (1 .. 8 slabs)
+    std::vector<vbrk::TileDesc> gtiles_dev;      // the same tiles as the device holds them: by slab class, heaviest first
+    int32_t gclass_begin[5] = {0, 0, 0, 0, 0};   // gathered tiles of slab class c are gtiles_dev[gclass_begin[c] .. gclass_begin[c+1])
+    std::vector<int32_t> group_gt_first;         // [n_groups] first gathered tile of a tall group packed that way, -1 otherwise
     std::vector<int32_t> gcol;           // per K-step of a gathered tile 32 columns of A (= rows of B), ascending, -1 = padding
     std::vector<vbrk::PanelDesc> panels;
     std::vector<int32_t> pk_row;         // host only: first B row of each granule of each physical K-step, -1 = padding

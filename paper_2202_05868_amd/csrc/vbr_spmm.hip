@@ -119,7 +119,6 @@ template <int DT, int S, int NS, int DA, bool GATHER = false>
 __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, const int ntile, unsigned char *smem)
 {
     static_assert(NS >= 2 && DA >= NS - 1, "A must be requested before the B panel of its K-step");
-    static_assert(!GATHER || S == 1, "column-gathered tiles are single slabs");
     constexpr int NA = S >= 4 ? S / 4 : 1;      // A loads per wave per K-step
     constexpr int NAS = DA + 1;
     constexpr int kAStage = S * kFragBytes;
@@ -393,8 +392,12 @@ __global__ void __launch_bounds__(kThreads) vbr_spmm_mixed_kernel(const Params p
     int tile, ntile;
     if (!map_workgroup(p.n_tiles, p.n_ntiles, tile, ntile)) return;
     const TileDesc td = p.tiles[tile];
-    if (td.group < 0) tile_body<DT, 1, NS, DA, true>(p, td, ntile, smem);        // column-gathered slab
-    else if (td.n_slabs <= 1) tile_body<DT, 1, NS, DA>(p, td, ntile, smem);
+    if (td.group < 0) {                   // column-gathered
+        if (td.n_slabs <= 1) tile_body<DT, 1, NS, DA, true>(p, td, ntile, smem);
+        else if (td.n_slabs <= 2) tile_body<DT, 2, NS, DA, true>(p, td, ntile, smem);
+        else if (td.n_slabs <= 4) tile_body<DT, 4, NS, DA, true>(p, td, ntile, smem);
+        else tile_body<DT, 8, NS, DA, true>(p, td, ntile, smem);
+    } else if (td.n_slabs <= 1) tile_body<DT, 1, NS, DA>(p, td, ntile, smem);
     else if (td.n_slabs <= 2) tile_body<DT, 2, NS, DA>(p, td, ntile, smem);
     else if (td.n_slabs <= 4) tile_body<DT, 4, NS, DA>(p, td, ntile, smem);
     else tile_body<DT, 8, NS, DA>(p, td, ntile, smem);
@@ -596,10 +599,6 @@ __global__ void __launch_bounds__(kPanelThreads) vbr_spmm_panel_kernel(const Pan
     }
 }
 
-#ifndef VBR_GNS
-#define VBR_GNS 2
-#define VBR_GDA 3
-#endif
 constexpr int kStages = 2;      // LDS ring of B panels
 constexpr int kStagesTall = 3;  // the same for tiles of 5 to 8 slabs (80 KiB of LDS, two workgroups per CU): measured 3 % (K = 16 384)
                                 // to 14 % (K = 8 192) faster than 2 on dense matrices; slower than 2 for every lower class
@@ -625,8 +624,17 @@ int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStrea
         case VBR_LAUNCH_TILE_MIXED:
             hipLaunchKernelGGL((vbr_spmm_mixed_kernel<DT, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
             break;
-        case VBR_LAUNCH_GATHER:
-            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, VBR_GNS, VBR_GDA, true>), grid, dim3(kThreads), 0, stream, p);
+        case VBR_LAUNCH_GATHER_1:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance, true>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        case VBR_LAUNCH_GATHER_2:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 2, kStages, kADistance, true>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        case VBR_LAUNCH_GATHER_4:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 4, kStages, kADistance, true>), grid, dim3(kThreads), 0, stream, p);
+            break;
+        case VBR_LAUNCH_GATHER_8:
+            hipLaunchKernelGGL((vbr_spmm_kernel<DT, 8, kStagesTall, kADistance, true>), grid, dim3(kThreads), 0, stream, p);
             break;
         case VBR_LAUNCH_TILE_1:
             hipLaunchKernelGGL((vbr_spmm_kernel<DT, 1, kStages, kADistance>), grid, dim3(kThreads), 0, stream, p);
@@ -661,7 +669,7 @@ extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
     struct Part { int64_t off; const void *src; size_t bytes; };
     static const unsigned char kZeros[256] = {0};
     const Part parts[10] = {
-        {L.tiles_off + (int64_t)(v->tiles.size() * sizeof(vbrk::TileDesc)), v->gtiles.data(), v->gtiles.size() * sizeof(vbrk::TileDesc)},
+        {L.tiles_off + (int64_t)(v->tiles.size() * sizeof(vbrk::TileDesc)), v->gtiles_dev.data(), v->gtiles_dev.size() * sizeof(vbrk::TileDesc)},
         {L.gcol_off, v->gcol.data(), v->gcol.size() * 4},
         {L.panels_off, v->panels.data(), v->panels.size() * sizeof(vbrk::PanelDesc)},
         {L.pk_meta_off, v->pk_meta.data(), v->pk_meta.size() * 4},
