@@ -9,6 +9,7 @@ Runs, one after the other, each as its own process and under its own time limit:
   2. ``rocprofv3 --pmc FETCH_SIZE``        on the same command with ``--no-ramp --steps 5 --warmup 2 --calib-copy``
   3. ``rocprofv3 --pmc WRITE_SIZE``        likewise
   4. ``rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAVE_CYCLES SQ_LDS_BANK_CONFLICT``  likewise
+  5. ``rocprofv3 --pmc TA_BUSY_avr SQ_BUSY_CU_CYCLES SQ_INSTS_VMEM_RD SQ_WAIT_ANY SQ_WAVE_CYCLES``  likewise
 
 and writes ``<out>/summary.txt``.  The kernel trace holds every dispatch of the run: the launches
 that let the clocks settle, the warm-up and the timed steps.  The summary therefore gives the
@@ -132,6 +133,27 @@ def main() -> int:
             if cs.get("SQ_BUSY_CU_CYCLES"):
                 text.append("  -> MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES) = %.1f %%  (%s)" % (
                     100.0 * cs.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / (4.0 * cs["SQ_BUSY_CU_CYCLES"]), k[k.find("vbr_spmm"):][:50]))
+        # the load path: how busy the texture-address unit is (every direct-to-LDS load goes through it)
+        ctrs = ["TA_BUSY_avr", "SQ_BUSY_CU_CYCLES", "SQ_INSTS_VMEM_RD", "SQ_WAIT_ANY", "SQ_WAVE_CYCLES"]
+        run(["rocprofv3", "--pmc"] + ctrs + ["-d", os.path.join(out_dir, "ta"), "-o", "p", "--"] + bench + pmc_tail[:-1],
+            os.path.join(out_dir, "ta.err"), 180)
+        con = sqlite3.connect(os.path.join(out_dir, "ta", "p_results.db"))
+        q = con.execute("select kernel_name, counter_name, avg(value), count(*) from counters_collection "
+                        "where kernel_name like '%vbr_spmm%' group by kernel_name, counter_name").fetchall()
+        text += ["", "## load path (per dispatch, average): rocprofv3 --pmc %s -d <out>/ta -o p -- %s %s" % (
+            " ".join(ctrs), shown, " ".join(pmc_tail[:-1]))]
+        per = {}
+        for k, c, val, cnt in q:
+            text.append("  %-60s %-28s %16.1f (n=%d)" % (k[k.find("vbr_spmm"):][:60], c, val, cnt))
+            per.setdefault(k, {})[c] = val
+        for k, cs in per.items():
+            if cs.get("SQ_BUSY_CU_CYCLES") and cs.get("SQ_INSTS_VMEM_RD"):
+                per_cu = cs["SQ_BUSY_CU_CYCLES"] / 256.0
+                text.append("  -> TA busy %.0f %% of the kernel's cycles (TA_BUSY_avr / (SQ_BUSY_CU_CYCLES / 256 CUs)); %.1f busy cycles and "
+                            "%.1f kernel cycles per vector-memory load instruction and CU; waves waiting %.0f %% of their time  (%s)" % (
+                                100.0 * cs.get("TA_BUSY_avr", 0.0) / per_cu, cs.get("TA_BUSY_avr", 0.0) * 256.0 / cs["SQ_INSTS_VMEM_RD"],
+                                cs["SQ_BUSY_CU_CYCLES"] / cs["SQ_INSTS_VMEM_RD"],
+                                100.0 * cs.get("SQ_WAIT_ANY", 0.0) / max(1.0, cs.get("SQ_WAVE_CYCLES", 1.0)), k[k.find("vbr_spmm"):][:50]))
     with open(os.path.join(out_dir, "summary.txt"), "w") as f:
         f.write("\n".join(text) + "\n")
     print("\n".join(text))
