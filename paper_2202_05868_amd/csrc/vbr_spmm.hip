@@ -39,6 +39,7 @@ struct Params {
     const int32_t *perm;
     const int32_t *gcol;      // column-gathered tiles: their column lists ...
     const int32_t *prow;      // ... and the list of the low rows their row positions refer to
+    int32_t b_fits32;         // the rows of B the matrix can touch span less than 4 GiB: 32-bit offsets from B suffice
     const uint16_t *vals;
     const uint16_t *zeros;    // 256 zero bytes: source of padding rows, padding lanes and columns >= N
     const uint16_t *zfrag;    // 1 KiB of zeros behind the last fragment: padding rows of the column-gathered tiles
@@ -230,12 +231,22 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
                 // the two row pointers of a load are computed on the scalar unit (a padding entry points
                 // at the kilobyte of zeros behind the values); a lane only selects its half's pointer and
                 // adds its column offset
+                if (p.b_fits32 && rb0.r[7] >= 0) {
+                    // all of B lies within 4 GiB and none of the wave's 8 entries is padding (the list
+                    // ascends, padding trails): scalar base + 32-bit lane offsets, the cheaper form of the load
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int e0 = rb0.r[2 * i], e1 = rb0.r[2 * i + 1];
-                    const char *p0 = e0 >= 0 ? Btile + (uint64_t)(uint32_t)e0 * ldb_bytes : zpad;
-                    const char *p1 = e1 >= 0 ? Btile + (uint64_t)(uint32_t)e1 * ldb_bytes : zpad;
-                    dma16((half ? p1 : p0) + b_coff[i], sb + 2 * i * kRowBytes);
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t o0 = (uint32_t)rb0.r[2 * i] * ldb_bytes, o1 = (uint32_t)rb0.r[2 * i + 1] * ldb_bytes;
+                        dma16_base((half ? o1 : o0) + b_coff[i], Btile, sb + 2 * i * kRowBytes);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int e0 = rb0.r[2 * i], e1 = rb0.r[2 * i + 1];
+                        const char *p0 = e0 >= 0 ? Btile + (uint64_t)(uint32_t)e0 * ldb_bytes : zpad;
+                        const char *p1 = e1 >= 0 ? Btile + (uint64_t)(uint32_t)e1 * ldb_bytes : zpad;
+                        dma16((half ? p1 : p0) + b_coff[i], sb + 2 * i * kRowBytes);
+                    }
                 }
             } else if (tile_fast && rb0.r[0] >= 0) {
                 const char *rowptr = Btile + (uint64_t)(uint32_t)rb0.r[0] * ldb_bytes;          // scalar, 64-bit
@@ -733,6 +744,7 @@ extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C
     pp.n_ntiles = (int32_t)((N + 127) / 128);
     p.gcol = reinterpret_cast<const int32_t *>(d + v->lay.gcol_off);
     p.zfrag = pp.zfrag;
+    p.b_fits32 = (v->n_cols * ldb * 2 + N * 2) < ((int64_t)1 << 32) ? 1 : 0;
     p.prow = pp.prow;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return v->dtype == VBR_F16 ? vbrk::launch_all<VBR_F16>(v, p, pp, stream) : vbrk::launch_all<VBR_BF16>(v, p, pp, stream);
