@@ -92,6 +92,8 @@ def main() -> int:
                     help="instead of the benchmark: blocked multiply vs CSR multiply on RMAT graphs, 8 .. 128 edges per "
                          "node x column blocks 64 / 128 / 256 (section 4.4.3); prints one JSON line")
     ap.add_argument("--small", action="store_true", help="with --landscape / --rmat-grid: a reduced grid (a minute)")
+    ap.add_argument("--denominators", action="store_true",
+                    help="instead of the benchmark: only the measured denominators, as one JSON line")
     ap.add_argument("--no-denominators", action="store_true",
                     help="skip the measured denominators (matrix-instruction issue rates, LDS operand rates, "
                          "direct-to-LDS load rate, HBM copy), which run outside the timed region")
@@ -117,6 +119,11 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.denominators:
+        print(json.dumps({"denominators": measure_denominators(torch, binding, dev),
+                          "note": "rates of single units measured with the library's probe loops (vbr_probe_launch), "
+                                  "16 waves per CU; flop/s for the matrix instructions, bytes/s otherwise"}))
+        return 0
     if args.landscape or args.rmat_grid:
         from paper_2202_05868_amd import experiments
         say = lambda msg: print(msg, file=sys.stderr, flush=True)
