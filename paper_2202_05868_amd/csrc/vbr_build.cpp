@@ -882,7 +882,11 @@ extern "C" int64_t vbr_get_tile_ksteps(const vbr_t *v, int64_t *out, int64_t cap
     return n;
 }
 
-extern "C" void vbr_free(vbr_t *v) { delete v; }
+extern "C" void vbr_free(vbr_t *v)
+{
+    if (v && v->release_dev) v->release_dev(v);
+    delete v;
+}
 
 extern "C" const char *vbr_strerror(int code)
 {

@@ -122,4 +122,12 @@ struct vbr {
     std::vector<int32_t> p_union;        // host only: ascending union of the column blocks of each panel
     vbrk::DeviceLayout lay;
     void *dev = nullptr;                 // uploaded buffer (caller-owned)
+    // A multiply of several launches forks them over side streams and joins them on the caller's
+    // stream (they write disjoint rows of C).  Created by vbr_upload on the device current then,
+    // released through `release_dev` by vbr_free; all opaque to the host-only translation units.
+    static constexpr int kSideStreams = 3;
+    void *side_stream[kSideStreams] = {nullptr, nullptr, nullptr};
+    void *ev_fork = nullptr;
+    void *ev_join[kSideStreams] = {nullptr, nullptr, nullptr};
+    void (*release_dev)(vbr *) = nullptr;
 };

@@ -5,6 +5,8 @@
 // rings of LDS slots with 128-bit direct-to-LDS loads, and issues v_mfma_f32_16x16x32 on them.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cstdlib>
 #include <cstdint>
 #include <type_traits>
 
@@ -616,14 +618,26 @@ constexpr int kStagesTall = 3;  // the same for tiles of 5 to 8 slabs (80 KiB of
 constexpr int kADistance = 3;   // K-steps the A fragments are requested ahead
 
 template <int DT>
-int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStream_t stream)
+int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStream_t caller)
 {
     Launch plan[VBR_MAX_LAUNCHES];
     const int n = plan_launches(v, base.N, plan);
     for (int i = 0; i < n; ++i)
         if (plan[i].grid > INT32_MAX) return VBR_EINVAL;
+    // Several launches write disjoint rows of C and are independent of each other: the first stays on
+    // the caller's stream, the others go to the side streams behind an event recorded on the caller's
+    // stream, and the caller's stream waits for each side stream's last launch.
+    static const bool serial = getenv("VBR_SPMM_SERIAL") != nullptr;
+    const bool fork = n > 1 && v->ev_fork && !serial;
+    if (fork) {
+        hipError_t e = hipEventRecord((hipEvent_t)v->ev_fork, caller);
+        for (int k = 0; e == hipSuccess && k < std::min(n - 1, (int)vbr::kSideStreams); ++k)
+            e = hipStreamWaitEvent((hipStream_t)v->side_stream[k], (hipEvent_t)v->ev_fork, 0);
+        if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
+    }
     for (int i = 0; i < n; ++i) {
         const Launch &L = plan[i];
+        hipStream_t stream = fork && i > 0 ? (hipStream_t)v->side_stream[(i - 1) % vbr::kSideStreams] : caller;
         Params p = base;
         p.tiles = base.tiles + L.first_tile;
         p.n_tiles = L.n_tiles;
@@ -663,6 +677,45 @@ int launch_all(const vbr *v, const Params &base, const PanelParams &pp, hipStrea
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
     }
+    if (fork) {
+        for (int k = 0; k < std::min(n - 1, (int)vbr::kSideStreams); ++k) {
+            hipError_t e = hipEventRecord((hipEvent_t)v->ev_join[k], (hipStream_t)v->side_stream[k]);
+            if (e == hipSuccess) e = hipStreamWaitEvent(caller, (hipEvent_t)v->ev_join[k], 0);
+            if (e != hipSuccess) { set_last_hip_error((int)e); return VBR_EHIP; }
+        }
+    }
+    return VBR_OK;
+}
+
+// Streams and events of the forked launches; vbr_free calls this through the handle.
+void release_device_objects(vbr *v)
+{
+    for (int k = 0; k < vbr::kSideStreams; ++k) {
+        if (v->ev_join[k]) (void)hipEventDestroy((hipEvent_t)v->ev_join[k]);
+        if (v->side_stream[k]) (void)hipStreamDestroy((hipStream_t)v->side_stream[k]);
+        v->ev_join[k] = v->side_stream[k] = nullptr;
+    }
+    if (v->ev_fork) (void)hipEventDestroy((hipEvent_t)v->ev_fork);
+    v->ev_fork = nullptr;
+    v->release_dev = nullptr;
+}
+
+int create_device_objects(vbr *v)
+{
+    if (v->ev_fork) return VBR_OK;
+    v->release_dev = release_device_objects;
+    hipEvent_t ev;
+    hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e == hipSuccess) v->ev_fork = ev;
+    for (int k = 0; e == hipSuccess && k < vbr::kSideStreams; ++k) {
+        hipStream_t st;
+        e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);       // default priority
+        if (e != hipSuccess) break;
+        v->side_stream[k] = st;
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e == hipSuccess) v->ev_join[k] = ev;
+    }
+    if (e != hipSuccess) { release_device_objects(v); set_last_hip_error((int)e); return VBR_EHIP; }
     return VBR_OK;
 }
 
@@ -699,7 +752,7 @@ extern "C" int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream)
     hipError_t e = hipStreamSynchronize(stream);
     if (e != hipSuccess) { vbrk::set_last_hip_error((int)e); return VBR_EHIP; }
     v->dev = buf_dev;
-    return VBR_OK;
+    return vbrk::create_device_objects(v);
 }
 
 extern "C" int vbr_spmm(const vbr_t *v, const void *B_dev, int64_t ldb, float *C_dev, int64_t ldc,

@@ -325,6 +325,54 @@ def test_runs_on_the_given_stream_and_in_a_captured_graph():
         check_c(c_graph.cpu().numpy().astype(np.float64), c_ref, s_ref, "graph replay %d" % rep)
 
 
+def test_forked_launches_keep_the_order_of_the_callers_stream_and_replay_in_a_graph():
+    # a multiply of several launches spreads them over the handle's own streams between an event
+    # recorded on the caller's stream and waits of the caller's stream: work queued before the call
+    # (the NaN fill) must be over before any launch writes, work queued after it (the clone) must
+    # see every row; a captured graph must carry the same fork and join
+    import torch
+    rng = np.random.default_rng(61)
+    w = synth.workload("rmat")
+    a, cb = w["A"], w["col_block"]
+    perm, rg = binding.sa1_reorder(a, cb, w["taus"][0])
+    v = binding.vbr_build(a, perm, rg, cb).upload("cuda:0")
+    k, n = w["B"].shape
+    assert len(v.launches(n)) >= 2, v.launches(n)
+    b = torch_io.bits_to_device(w["B"], w["dtype"])
+    c_ref, s_ref = oracle.spmm(a, w["B"])
+    side = torch.cuda.Stream()                        # default priority
+    c = torch.empty((a["n_rows"], n), dtype=torch.float32, device="cuda:0")
+    side.wait_stream(torch.cuda.current_stream())
+    results = []
+    with torch.cuda.stream(side):
+        for _ in range(6):
+            c.fill_(float("nan"))
+            v.spmm(b, c)
+            results.append(c.clone())
+    side.synchronize()
+    check_c(results[0].cpu().numpy().astype(np.float64), c_ref, s_ref, "forked launches, first call")
+    for i, r in enumerate(results[1:]):
+        assert torch.equal(r, results[0]), "call %d differs from the first" % (i + 1)
+
+    c_graph = torch.full_like(c, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        v.spmm(b, c_graph)
+    for rep in range(3):
+        b_bits = synth.dense_rhs(rng, k, n, w["dtype"])
+        b.copy_(torch_io.bits_to_device(b_bits, w["dtype"]))       # eager work between the replays
+        c_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        c_eager = v.spmm(b, torch.empty_like(c_graph))
+        torch.cuda.synchronize()
+        assert torch.equal(c_graph, c_eager), "replay %d differs from the eager launches" % rep
+    c_ref, s_ref = oracle.spmm(a, b_bits)
+    check_c(c_graph.cpu().numpy().astype(np.float64), c_ref, s_ref, "graph replay")
+
+
 def test_right_hand_side_larger_than_4_gib():
     # B is a 256-column window of a 70 000 x 32 776 tensor (4.6 GB): row bases need 64 bits
     import torch
