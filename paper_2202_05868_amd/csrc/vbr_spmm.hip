@@ -330,8 +330,8 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
 
         // ---- software pipeline over the K-steps.  Issue order, as if the loop had started NS-1
         // iterations early: A(0 .. DA-NS), then B(t), A(DA-NS+1+t) for t = 0 .. NS-2; iteration ks
-        // then issues B(ks+NS-1), A(ks+DA).  K-steps past the end re-load the last one, so that the
-        // number of loads in flight, which the vmcnt wait relies on, never changes.
+        // then issues B(ks+NS-1), A(ks+DA).  The prologue re-loads the last K-step for K-steps past the
+        // end of a very short tile, so that the loop always starts with the same loads in flight.
         rb0 = load_rows(0);
         rb1 = load_rows(1);
 #pragma unroll
@@ -345,15 +345,19 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
         }
         int bslot = 0, aslot = 0;
         for (int ks = 0; ks < n_ks; ++ks) {
-            wait_stage(ks);                        // this wave's loads of K-step ks have landed
+            // The last iterations issue nothing for K-steps past the end (a short tile would spend a
+            // tenth of its loads there); from the first iteration whose predecessors left loads out,
+            // the counted wait no longer holds and the wave waits for everything it has in flight.
+            if (ks + DA > n_ks) wait_vmcnt<0>();
+            else wait_stage(ks);                   // this wave's loads of K-step ks have landed
             __builtin_amdgcn_s_barrier();          // ... and everybody else's; the slots of K-step ks-1 are free
             asm volatile("" ::"s"(rb0.r[0]));      // the scalar row lookup is waited for here, not behind the LDS reads
             read_frags(bslot, aslot);
             // the load path is what bounds the kernel: a wave that is about to issue its loads goes
             // ahead of the waves that are multiplying (measured: 3-4 % on the 16-row workload)
             __builtin_amdgcn_s_setprio(3);
-            issue_b(ks + NS - 1, bslot == 0 ? NS - 1 : bslot - 1);
-            issue_a(ks + DA, aslot == 0 ? NAS - 1 : aslot - 1);
+            if (ks + NS - 1 < n_ks) issue_b(ks + NS - 1, bslot == 0 ? NS - 1 : bslot - 1);
+            if (ks + DA < n_ks) issue_a(ks + DA, aslot == 0 ? NAS - 1 : aslot - 1);
             __builtin_amdgcn_s_setprio(0);
             multiply();
             rb0 = rb1;
