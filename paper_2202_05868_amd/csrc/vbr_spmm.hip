@@ -379,9 +379,10 @@ __device__ __forceinline__ void tile_body(const Params &p, const TileDesc td, co
             for (int f = 0; f < 4; ++f) {
                 const int n = n0 + wave * kWaveN + 16 * f + 4 * q;
                 if (n >= p.N) continue;
-                // tall tiles store around the caches' write allocation (measured on the dense 4096 x 16384
-                // x 4096 product: 0.44 -> 0.37 ms; no gain, or a small loss, for the lower classes)
-                if constexpr (S >= 8) __builtin_nontemporal_store(acc[s][f], reinterpret_cast<float4v *>(crow + n));
+                // tall tiles and gathered tiles store around the caches' write allocation (measured: the
+                // dense 4096 x 16384 x 4096 product 0.44 -> 0.37 ms, the graph workload 213 -> 204 us; no
+                // gain, or a small loss, for the lower classes on whole column blocks)
+                if constexpr (S >= 8 || GATHER) __builtin_nontemporal_store(acc[s][f], reinterpret_cast<float4v *>(crow + n));
                 else *reinterpret_cast<float4v *>(crow + n) = acc[s][f];
             }
         }

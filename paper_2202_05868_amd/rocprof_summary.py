@@ -85,6 +85,12 @@ def main() -> int:
             short, len(all_d), sum(all_d) / len(all_d), len(tim_d), sum(tim_d) / max(1, len(tim_d))))
         step_us += sum(tim_d) / max(1, args.steps)
     text.append("  kernel time per timed step (sum over its launches): %.3f us" % step_us)
+    if per_step > 1:
+        spans = [max(e for _, _, e in timed[i:i + per_step]) - min(b for _, b, _ in timed[i:i + per_step])
+                 for i in range(0, len(timed), per_step)]
+        text.append("  the launches of one call run side by side (the first on the caller's stream, the others on the handle's own")
+        text.append("  streams), so their durations overlap: first start to last end of a timed step, average %.3f us" % (
+            sum(spans) / len(spans) / 1e3))
     text.append("bench.py in the same run: ms_per_step %.4f (HIP events around the %d timed steps), value %.1f %s, clock-ramp launches %d" % (
         bj["ms_per_step"], args.steps, bj["value"], bj["unit"], bj["clock_ramp_launches"]))
     text.append("(under the profiler every dispatch is followed by a completion signal, so the GPU idles between launches and")
