@@ -1,8 +1,14 @@
 // vbr_spmm on gfx950: C = A.B with A in packed VBR form (section 4.4.1 of the paper: every stored
-// block is multiplied as a dense product on the matrix units).  One launch per slab class; each
-// workgroup owns up to 8 slabs of 16 rows of ONE row group and a 256-column tile of C, walks the
-// group's block list in K-steps of 32 B rows, brings the gathered B rows and the A fragments into
-// rings of LDS slots with 128-bit direct-to-LDS loads, and issues v_mfma_f32_16x16x32 on them.
+// block is multiplied as a dense product on the matrix units).  Three kernels share one scheme: a
+// workgroup owns some slabs of 16 rows and a column tile of C, walks a list of K-steps of 32 B rows,
+// brings the gathered B rows and the A fragments into rings of LDS slots with 128-bit direct-to-LDS
+// loads, and issues v_mfma_f32_16x16x32 on them.
+//   tile kernel    up to 8 slabs of ONE row group x 256 columns; K-steps = the group's column blocks
+//                  (one launch per slab class, or one mixed launch for small matrices)
+//   gathered tiles the same kernel with K-steps = the single columns its rows touch: slabs cut from the
+//                  rows of low groups, and tiles of tall groups whose blocks are mostly fill-in
+//   panel kernel   8 slabs of low groups x 128 columns walking the union of their column blocks
+// The launches of one call are independent and are spread over the handle's streams (launch_all).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
