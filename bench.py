@@ -82,6 +82,10 @@ def main() -> int:
                     help="skip the CSR comparator kernel (the stand-in for the sparse-library routine)")
     ap.add_argument("--no-dense-baseline", action="store_true",
                     help="skip the dense product on the zero-filled matrix (run by default for c2 and c4)")
+    ap.add_argument("--dense", action="store_true",
+                    help="measure the dense product on the zero-filled matrix instead (A stored as one dense VBR, groups "
+                         "of 128 rows, every block kept, no reordering): the comparison the target configuration names, "
+                         "as a workload of its own so that it can be profiled; no CSR / dense / CPU baselines")
     ap.add_argument("--select-tau", action="store_true",
                     help="take the threshold from the blocking curve (tau = 0.1 .. 1) by the paper's rule, average block "
                          "height nearest to the matrix's own block height, instead of the workload's fixed tau")
@@ -103,6 +107,9 @@ def main() -> int:
     args = ap.parse_args()
     if args.timed_only:
         args.no_cpu_baseline = args.no_csr_baseline = args.no_dense_baseline = args.no_denominators = True
+    if args.dense:
+        args.no_cpu_baseline = args.no_csr_baseline = args.no_dense_baseline = True
+        args.select_tau = False
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (row groups shard "
               "without any exchange step; nothing here uses a second GPU)" % args.gpus, file=sys.stderr)
@@ -154,9 +161,25 @@ def main() -> int:
                      "rho_after": (a["nnz"] / np.maximum(cur["stored_elems"], 1)).tolist(),
                      "selected_tau": tau, "curve_s": time.perf_counter() - ts}
 
+    def zero_filled(m):
+        """the matrix with every entry stored (explicit zeros), as CSR"""
+        rows, cols = m["n_rows"], m["n_cols"]
+        d = dict(m)
+        d["row_ptr"] = np.arange(rows + 1, dtype=np.int64) * cols
+        d["col_idx"] = np.tile(np.arange(cols, dtype=np.int32), rows)
+        d["vals"] = np.ascontiguousarray(synth.dense_bits(m).reshape(-1))
+        d["nnz"] = rows * cols
+        return d
+
     # ---- one-off host work of the path
     t0 = time.perf_counter()
-    perm, rg = binding.sa1_reorder(a, cb, tau)
+    if args.dense:
+        a = zero_filled(a)
+        tau = None
+        perm = np.arange(a["n_rows"], dtype=np.int32)
+        rg = np.arange(0, a["n_rows"] + 128, 128, dtype=np.int32).clip(max=a["n_rows"])
+    else:
+        perm, rg = binding.sa1_reorder(a, cb, tau)
     t1 = time.perf_counter()
     v = binding.vbr_build(a, perm, rg, cb)
     t2 = time.perf_counter()
@@ -311,7 +334,8 @@ def main() -> int:
         "dtype": w["dtype"],
         "accumulate_dtype": "f32 (MFMA)",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload] + ("" if not args.clean else " (noise-free)"),
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + ("" if not args.clean else " (noise-free)") +
+                               ("" if not args.dense else " -- ZERO-FILLED: every entry stored, groups of 128 rows, no reordering"),
                    "N": n, "col_block": cb, "tau": tau, "parallelism": "1 GPU"},
         "nnz_effective_tflops": tflops_nnz,
         "executed_tflops": tflops_exec,
@@ -364,11 +388,7 @@ def main() -> int:
         # the dense product on the zero-filled matrix (the comparison the target config names): the
         # same hand-written tile kernel, A stored as one dense VBR (128-row groups, every block kept)
         m_rows, k_cols = a["n_rows"], a["n_cols"]
-        dense = dict(a)
-        dense["row_ptr"] = np.arange(m_rows + 1, dtype=np.int64) * k_cols
-        dense["col_idx"] = np.tile(np.arange(k_cols, dtype=np.int32), m_rows)
-        dense["vals"] = np.ascontiguousarray(synth.dense_bits(a).reshape(-1))
-        dense["nnz"] = m_rows * k_cols
+        dense = zero_filled(a)
         vd = binding.vbr_build(dense, np.arange(m_rows, dtype=np.int32),
                                np.arange(0, m_rows + 1, 128, dtype=np.int32), cb)
         del dense

@@ -47,6 +47,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--clean", action="store_true")
+    ap.add_argument("--dense", action="store_true", help="the dense product on the zero-filled matrix (bench.py --dense)")
     ap.add_argument("--out", required=True)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--no-counters", action="store_true", help="kernel trace only")
@@ -54,14 +55,15 @@ def main() -> int:
     out_dir = os.path.abspath(args.out)
     os.makedirs(out_dir, exist_ok=True)
     bench = ["python3", os.path.join(ROOT, "bench.py"), "--workload", args.workload, "--timed-only"]
-    if args.clean:
-        bench.append("--clean")
-    shown = "python3 bench.py --workload %s --timed-only%s" % (args.workload, " --clean" if args.clean else "")
+    flags = (" --clean" if args.clean else "") + (" --dense" if args.dense else "")
+    bench += flags.split()
+    shown = "python3 bench.py --workload %s --timed-only%s" % (args.workload, flags)
     pmc_tail = ["--no-ramp", "--steps", "5", "--warmup", "2", "--calib-copy"]
-    text = ["# rocprofv3 summary: vbr_spmm on workload %s%s (MI355X, gfx950)" % (args.workload, " (noise-free)" if args.clean else ""),
+    text = ["# rocprofv3 summary: vbr_spmm on workload %s%s (MI355X, gfx950)" % (
+                args.workload, (" (noise-free)" if args.clean else "") + (" stored zero-filled: the dense product" if args.dense else "")),
             "",
             "made by             : python -m paper_2202_05868_amd.rocprof_summary --workload %s%s --out <out>" % (
-                args.workload, " --clean" if args.clean else ""),
+                args.workload, flags),
             "kernel trace command: cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d <out>/trace -o t -- %s --steps %d" % (shown, args.steps)]
 
     bj = run(["rocprofv3", "--kernel-trace", "--stats", "-d", os.path.join(out_dir, "trace"), "-o", "t", "--"] + bench +
