@@ -373,6 +373,36 @@ def test_forked_launches_keep_the_order_of_the_callers_stream_and_replay_in_a_gr
     check_c(c_graph.cpu().numpy().astype(np.float64), c_ref, s_ref, "graph replay")
 
 
+def test_two_handles_on_two_streams_at_the_same_time():
+    # every handle has its own side streams and events, so two multiplies of several launches each
+    # may be in flight at once from different caller streams
+    import torch
+    rng = np.random.default_rng(62)
+    w = synth.workload("rmat")
+    a, cb = w["A"], w["col_block"]
+    perm, rg = binding.sa1_reorder(a, cb, w["taus"][0])
+    k, n = w["B"].shape
+    hs = [binding.vbr_build(a, perm, rg, cb).upload("cuda:0") for _ in range(2)]
+    assert len(hs[0].launches(n)) >= 2
+    bs = [torch_io.bits_to_device(synth.dense_rhs(rng, k, n, w["dtype"]), w["dtype"]) for _ in range(2)]
+    alone = [hs[i].spmm(bs[i], torch.empty((a["n_rows"], n), dtype=torch.float32, device="cuda:0")) for i in range(2)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]          # default priority
+    cs = [torch.full_like(alone[0], float("nan")) for _ in range(2)]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    for _ in range(5):
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                cs[i].fill_(float("nan"))
+                hs[i].spmm(bs[i], cs[i])
+    for st in streams:
+        st.synchronize()
+    for i in range(2):
+        assert torch.equal(cs[i], alone[i]), "handle %d: concurrent result differs from the one computed alone" % i
+        hs[i].close()
+
+
 def test_right_hand_side_larger_than_4_gib():
     # B is a 256-column window of a 70 000 x 32 776 tensor (4.6 GB): row bases need 64 bits
     import torch
