@@ -205,13 +205,17 @@ int build_impl(const vbr_csr_t *csr, const int32_t *perm, const int32_t *row_gro
                     if (!placed[j] && cnt[j]++ == 0) hit.push_back(j);
                 }
             }
-            std::sort(hit.begin(), hit.end());
+            // the followers join in rising order; only they are sorted (the candidates are thousands per
+            // leader on an unstructured matrix, the followers few)
+            size_t n_pass = 0;
             for (const int32_t j : hit) {
                 const int32_t gj = low_groups[j];
                 const int64_t I = cnt[j], lj = v->blk_ptr[gj + 1] - v->blk_ptr[gj];
                 cnt[j] = 0;
-                if (2 * I >= std::min(li, lj)) { placed[j] = 1; order.push_back(j); ++followers; }
+                if (2 * I >= std::min(li, lj)) hit[n_pass++] = j;
             }
+            std::sort(hit.begin(), hit.begin() + (std::ptrdiff_t)n_pass);
+            for (size_t k = 0; k < n_pass; ++k) { placed[hit[k]] = 1; order.push_back(hit[k]); ++followers; }
             if (++leaders == 512 && followers < 64) clustering = false;
         }
         // A cluster of two slabs' worth of rows or more begins and ends on a slab boundary (the list is
