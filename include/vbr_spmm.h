@@ -116,9 +116,9 @@ int64_t vbr_device_bytes(const vbr_t *v);
  * (a hipStream_t, NULL = default stream) and wait for the copy.  The handle keeps the pointer;
  * the buffer must outlive every vbr_spmm on this handle.  The library allocates no device memory.
  * Any col_block >= 1 is taken; widths that are multiples of 8 take the fast gather path.
- * The first upload of a handle also creates, on the current device, three streams of default
- * priority and four events (vbr_free destroys them): a multiply of several launches spreads them
- * over these streams, see vbr_spmm.
+ * For a matrix that needs more than one kind of kernel, the first upload of a handle also creates,
+ * on the current device, three streams of default priority and four events (vbr_free destroys
+ * them): a multiply of several launches spreads them over these streams, see vbr_spmm.
  */
 int vbr_upload(vbr_t *v, void *buf_dev, void *hip_stream);
 

@@ -714,6 +714,11 @@ void release_device_objects(vbr *v)
 int create_device_objects(vbr *v)
 {
     if (v->ev_fork) return VBR_OK;
+    // a matrix with one kind of work is one launch whatever N is: nothing to spread
+    int kinds = v->panels.empty() ? 0 : 1;
+    for (int c = 0; c < 4; ++c)
+        kinds += (v->class_begin[c + 1] > v->class_begin[c]) + (v->gclass_begin[c + 1] > v->gclass_begin[c]);
+    if (kinds <= 1) return VBR_OK;
     v->release_dev = release_device_objects;
     hipEvent_t ev;
     hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
